@@ -1,0 +1,170 @@
+/*
+ * slapo_mi355x -- one transformer layer's training step (forward + backward) in the form a Slapo
+ * schedule rewrites it to, as hand-written HIP kernels for gfx950 behind a C ABI.
+ *
+ * The scheduled layer (paper section 2.2 and the appendix schedule) consists of
+ *   - one linear producing the concatenated Q,K,V (three nn.Linear fused into one),
+ *   - a fused softmax-attention kernel working block by block (flash attention),
+ *   - the output and second FFN linears with their bias "decomposed" out of the matmul,
+ *   - F.gelu(bias + x) fused into the first FFN linear,
+ *   - LayerNorm(dropout(bias + x) + residual) fused into one kernel after both blocks,
+ * and the backward of all of these, which the paper leaves to autograd and this library derives
+ * by hand.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, 16-byte aligned, row-major with
+ *     the last index contiguous. The descriptor and the pointer tables are HOST structs.
+ *   - Weights use the nn.Linear layout [out_features, in_features] (paper Fig. 3 caption).
+ *   - `stream` is a hipStream_t passed as void*; all work is enqueued there, nothing synchronises,
+ *     nothing is allocated or freed, no pointer is kept after the call returns.
+ *   - Return value: SLAPO_OK (0) or a negative slapo_status. Argument checks run before the first
+ *     HIP call, so they behave the same on a host without a GPU. Nothing throws or aborts.
+ *   - Same inputs and seed give bitwise identical outputs (no floating-point atomics anywhere).
+ *   - Element type: SLAPO_BF16 (bf16 storage, fp32 accumulation and fp32 elementwise math) or
+ *     SLAPO_FP32 (fp32 everywhere; a correctness mode with simple kernels, not a tuned one).
+ */
+#ifndef SLAPO_MI355X_H
+#define SLAPO_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SLAPO_OK = 0,
+  SLAPO_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  SLAPO_ERR_SHAPE = -2,       /* non-positive size, hidden % heads != 0, dropout_p not in [0,1) */
+  SLAPO_ERR_UNSUPPORTED = -3, /* head dim not 64/128, hidden > 4096, unknown enum value        */
+  SLAPO_ERR_ALIGN = -4,       /* pointer not 16-byte aligned / size not a multiple of 8        */
+  SLAPO_ERR_WORKSPACE = -5,   /* reserved                                                      */
+  SLAPO_ERR_HIP = -6          /* a kernel launch reported an error                             */
+} slapo_status;
+
+enum { SLAPO_BF16 = 0, SLAPO_FP32 = 1 };
+enum { SLAPO_GELU_ERF = 0, SLAPO_RELU = 1 };
+
+/* Layer description (host struct). hidden/heads must be 64 or 128; hidden, ffn multiples of 8;
+ * hidden <= 4096. */
+typedef struct {
+  int32_t batch, seq, hidden, heads, ffn;
+  int32_t causal;           /* 1: query i sees keys j <= i                                     */
+  float dropout_p;          /* probability of dropping, in [0,1); applied at the two fused
+                               bias+dropout+residual sites, not on attention probabilities     */
+  uint64_t seed;            /* dropout seed (Philox key)                                       */
+  int32_t dtype;            /* SLAPO_BF16 | SLAPO_FP32: activations, weights and gradients     */
+  int32_t act;              /* SLAPO_GELU_ERF (0.5 u (1 + erf(u/sqrt 2))) | SLAPO_RELU         */
+  int32_t pre_ln;           /* 0: y = LN(x + f(x)) (BERT); 1: y = x + f(LN(x)) (GPT/OPT)       */
+  int32_t layer_id;         /* mixed into the dropout counter so stacked layers differ         */
+  float ln_eps;             /* LayerNorm epsilon (inside the square root)                      */
+  int32_t accumulate_grads; /* 0: overwrite parameter gradients, 1: add to them                */
+} slapo_layer_desc;
+
+/* Parameters: wqkv [3H,H] = [Wq;Wk;Wv] stacked on the output dim, bqkv [3H], wo [H,H], bo [H],
+ * ln1_g/ln1_b [H], w1 [F,H], b1 [F], w2 [H,F], b2 [H], ln2_g/ln2_b [H].
+ * Post-LN: ln1 follows the attention block, ln2 follows the FFN block.
+ * Pre-LN:  ln1 precedes the attention block, ln2 precedes the FFN block. */
+typedef struct {
+  const void *wqkv, *bqkv, *wo, *bo, *ln1_g, *ln1_b, *w1, *b1, *w2, *b2, *ln2_g, *ln2_b;
+} slapo_layer_params;
+typedef struct {
+  void *wqkv, *bqkv, *wo, *bo, *ln1_g, *ln1_b, *w1, *b1, *w2, *b2, *ln2_g, *ln2_b;
+} slapo_layer_grads;
+
+/* Sizes in bytes of the two caller-provided device buffers: `saved` carries activations from
+ * slapo_layer_fwd to slapo_layer_bwd (QKV, attention output, logsumexp, pre-norm sums, LayerNorm
+ * statistics, FFN pre-activation and activation) and must stay untouched in between; `scratch` is
+ * free for reuse as soon as a call's work has completed on the stream. */
+int slapo_layer_workspace(const slapo_layer_desc *desc, size_t *saved_bytes, size_t *scratch_bytes);
+
+/* Named regions inside `saved`, for tests and tools. Writes byte offset and byte length; returns
+ * SLAPO_ERR_UNSUPPORTED if the region does not exist for this wiring. Names: "qkv" [T,3H], "attn"
+ * [T,H], "lse" [B,heads,S] fp32, "z1" [T,H], "n1" (pre-LN) [T,H], "y1" (post-LN) / "n2" (pre-LN)
+ * [T,H], "u" [T,F], "g" [T,F], "z2" (post-LN) [T,H], "mu1","rstd1","mu2","rstd2" [T] fp32. */
+int slapo_layer_saved_region(const slapo_layer_desc *desc, const char *name, size_t *offset, size_t *bytes);
+
+/* Forward of the scheduled layer (section 2.2 steps 1-2, appendix schedule):
+ *   post-LN: QKV = x Wqkv^T + bqkv; A = attention(QKV); Z1 = x + drop0(A Wo^T + bo); Y1 = LN1(Z1);
+ *            G = act(Y1 W1^T + b1); Z2 = Y1 + drop1(G W2^T + b2); y = LN2(Z2)
+ *   pre-LN:  N1 = LN1(x); QKV from N1; Z1 = x + drop0(A Wo^T + bo); N2 = LN2(Z1);
+ *            G = act(N2 W1^T + b1); y = Z1 + drop1(G W2^T + b2)
+ * x, y: [B,S,H]. seqlens: device int32 [B] with 1 <= seqlens[b] <= S (keys j >= seqlens[b] are
+ * hidden from every query of sample b), or NULL for no padding mask; may be combined with causal. */
+int slapo_layer_fwd(const slapo_layer_desc *desc, const slapo_layer_params *params, const void *x,
+                    const int32_t *seqlens, void *y, void *saved, void *scratch, void *stream);
+
+/* Backward: given dy = dL/dy [B,S,H] and the `saved` buffer of the matching forward, writes
+ * dx [B,S,H] and the twelve parameter gradients (same shapes and element type as the parameters).
+ * The dropout masks are regenerated from (seed, layer_id, site, element index), never stored. */
+int slapo_layer_bwd(const slapo_layer_desc *desc, const slapo_layer_params *params, const void *x,
+                    const int32_t *seqlens, const void *dy, const void *saved, void *dx,
+                    const slapo_layer_grads *grads, void *scratch, void *stream);
+
+const char *slapo_status_string(int status);
+
+/* ---- building blocks, exported for per-kernel tests and measurement ---------------------------- */
+
+/* GEMM C[M,N] = op(A) op(B) with fp32 accumulation and a fused epilogue.
+ *   layout 0 (NT): A [M,K], B [N,K]   -- forward linears x W^T (fused QKV, output, FFN)
+ *   layout 1 (NN): A [M,K], B [K,N]   -- input gradients dY W
+ *   layout 2 (TN): A [K,M], B [K,N]   -- weight gradients dY^T X
+ *   epilogue 0: C = acc                       1: C = acc + bias[n]
+ *            2: aux_out = acc + bias[n]; C = act(aux_out)    (F.gelu(bias + x), appendix schedule)
+ *            3: C = acc * act'(aux_in[m,n])   4: C = acc + aux_in[m,n]  (aux_in may alias C)
+ * M, N, K > 0; K-contiguous operands need K % 8 == 0, M/N-contiguous ones M % 8 / N % 8 == 0;
+ * N % 8 == 0. */
+int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K,
+               const void *A, const void *B, void *C, const void *bias, const void *aux_in,
+               void *aux_out, void *stream);
+
+/* Fused softmax attention over the packed projection qkv [B,S,3H] (Q | K | V on the last axis,
+ * head a owning columns a*d..a*d+d-1 of each): out [B,S,H], lse [B,heads,S] fp32 holding
+ * log sum_j exp(q_i.k_j/sqrt(d)) over the visible keys (natural log). Uses desc->batch, seq, hidden,
+ * heads, causal, dtype. The S x S matrix never reaches memory (section 2.2 step 2). */
+int slapo_attn_fwd(const slapo_layer_desc *desc, const void *qkv, const int32_t *seqlens, void *out,
+                   float *lse, void *stream);
+
+/* Backward of slapo_attn_fwd: recomputes probabilities from lse; delta [B,heads,S] fp32 is scratch
+ * for rowsum(dout*out). Writes the packed dqkv [B,S,3H]. */
+int slapo_attn_bwd(const slapo_layer_desc *desc, const void *qkv, const int32_t *seqlens,
+                   const void *out, const void *dout, const float *lse, float *delta, void *dqkv,
+                   void *stream);
+
+/* z = res + keep * (r + bias) / (1 - p)   (bias, dropout, residual; skipped if r == NULL, then z := res)
+ * out = LayerNorm(z; gamma, beta), mu/rstd [T] fp32   (skipped if gamma == NULL)
+ * T rows of H elements. z_out may be NULL when only `out` is wanted (r == NULL case).
+ * site selects the dropout stream (0 after attention, 1 after the FFN). */
+int slapo_bdrln_fwd(const slapo_layer_desc *desc, int site, int64_t T, const void *r, const void *bias,
+                    const void *res, const void *gamma, const void *beta, void *z_out, void *out,
+                    float *mu, float *rstd, void *stream);
+
+/* Backward of the fused pattern. With gamma != NULL: dz = dres_in + LayerNorm'(dout; z, mu, rstd, gamma)
+ * and partial sums of dgamma = sum_t dout*xhat, dbeta = sum_t dout; with gamma == NULL: dz = dout
+ * (+ dres_in). If dr_out != NULL: dr = dz * keep / (1-p) (mask regenerated) and partial sums of
+ * dbias = sum_t dr. dz_out may be NULL. partials: fp32 [nblk, 3, H] (rows: dgamma, dbeta, dbias) with
+ * nblk = slapo_bdrln_bwd_blocks(T); reduce them with slapo_colreduce_partials. */
+int slapo_bdrln_bwd(const slapo_layer_desc *desc, int site, int64_t T, const void *dout, const void *z,
+                    const float *mu, const float *rstd, const void *gamma, const void *dres_in,
+                    void *dz_out, void *dr_out, float *partials, void *stream);
+int slapo_bdrln_bwd_blocks(int64_t T);
+
+/* Column sums of a [T,N] matrix in two deterministic stages: partials fp32 [nblk,N] with
+ * nblk = slapo_colsum_blocks(T), then slapo_colreduce_partials. */
+int slapo_colsum_partials(int dtype, int64_t T, int64_t N, const void *a, float *partials, void *stream);
+int slapo_colsum_blocks(int64_t T);
+/* out[n] (element type dtype) = (accumulate ? out[n] : 0) + sum_i partials[i*stride + n], i < nblk. */
+int slapo_colreduce_partials(int dtype, int64_t nblk, int64_t stride, int64_t N, const float *partials,
+                             void *out, int accumulate, void *stream);
+
+/* Writes the keep decisions (1 = kept, 0 = dropped) of one dropout site as bytes [T*H]:
+ * element e = t*H + c uses Philox4x32-10 with counter (lo32(e>>3), hi32(e>>3), site, layer_id),
+ * key (lo32(seed), hi32(seed)), 16-bit draw (out[(e&7)>>1] >> 16*(e&1)) & 0xffff, kept iff
+ * draw >= round(p * 65536). */
+int slapo_dropout_mask(const slapo_layer_desc *desc, int site, int64_t T, uint8_t *mask, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLAPO_MI355X_H */

@@ -1,0 +1,383 @@
+// C ABI of the library: argument validation, layout of the `saved` / `scratch` buffers and the
+// sequence of kernel launches that makes up one layer forward / backward. Host code only.
+#include <string.h>
+
+#include "../../include/slapo.h"
+#include "kernels.h"
+
+using namespace slapo;
+
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_desc(const slapo_layer_desc* d) {
+  if (!d) return SLAPO_ERR_NULL;
+  if (d->batch <= 0 || d->seq <= 0 || d->hidden <= 0 || d->heads <= 0 || d->ffn <= 0) return SLAPO_ERR_SHAPE;
+  if (d->hidden % d->heads != 0) return SLAPO_ERR_SHAPE;
+  if (!(d->dropout_p >= 0.f && d->dropout_p < 1.f)) return SLAPO_ERR_SHAPE;
+  if (!(d->ln_eps > 0.f)) return SLAPO_ERR_SHAPE;
+  if (d->hidden % 8 != 0 || d->ffn % 8 != 0) return SLAPO_ERR_ALIGN;
+  const int hd = d->hidden / d->heads;
+  if (hd != 64 && hd != 128) return SLAPO_ERR_UNSUPPORTED;
+  if (d->hidden > 4096) return SLAPO_ERR_UNSUPPORTED;
+  if (d->dtype != SLAPO_BF16 && d->dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (d->act != SLAPO_GELU_ERF && d->act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
+  if ((d->causal != 0 && d->causal != 1) || (d->pre_ln != 0 && d->pre_ln != 1)) return SLAPO_ERR_UNSUPPORTED;
+  if ((int64_t)d->batch * d->seq * 3 * d->hidden >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  if ((int64_t)d->batch * d->seq * d->ffn >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  return SLAPO_OK;
+}
+
+DropoutParams make_dropout(const slapo_layer_desc* d, int site) {
+  DropoutParams dp;
+  dp.key0 = (uint32_t)(d->seed & 0xffffffffu);
+  dp.key1 = (uint32_t)(d->seed >> 32);
+  dp.site = (uint32_t)site;
+  dp.layer = (uint32_t)d->layer_id;
+  dp.thr = (uint32_t)llround((double)d->dropout_p * 65536.0);
+  dp.scale = 1.0f / (1.0f - d->dropout_p);
+  return dp;
+}
+
+int finish() { return hipGetLastError() == hipSuccess ? SLAPO_OK : SLAPO_ERR_HIP; }
+
+// byte offsets of the regions of `saved`
+struct SavedLayout {
+  size_t qkv, attn, lse, z1, n1, y1, u, g, z2, mu1, rstd1, mu2, rstd2, total;
+};
+SavedLayout saved_layout(const slapo_layer_desc* d) {
+  const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
+  const size_t T = (size_t)d->batch * d->seq, H = d->hidden, F = d->ffn;
+  SavedLayout L;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };
+  L.qkv = take(T * 3 * H * eb);
+  L.attn = take(T * H * eb);
+  L.lse = take((size_t)d->batch * d->heads * d->seq * 4);
+  L.z1 = take(T * H * eb);
+  L.n1 = d->pre_ln ? take(T * H * eb) : (size_t)-1;
+  L.y1 = take(T * H * eb);  // post-LN: LN1 output; pre-LN: LN2 output ("n2")
+  L.u = take(T * F * eb);
+  L.g = take(T * F * eb);
+  L.z2 = d->pre_ln ? (size_t)-1 : take(T * H * eb);
+  L.mu1 = take(T * 4);
+  L.rstd1 = take(T * 4);
+  L.mu2 = take(T * 4);
+  L.rstd2 = take(T * 4);
+  L.total = o;
+  return L;
+}
+
+struct ScratchLayout {
+  size_t t0, t1, t2, du, dqkv, delta, part_row, part_col, total;
+};
+ScratchLayout scratch_layout(const slapo_layer_desc* d) {
+  const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
+  const size_t T = (size_t)d->batch * d->seq, H = d->hidden, F = d->ffn;
+  ScratchLayout L;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };
+  L.t0 = take(T * H * eb);
+  L.t1 = take(T * H * eb);
+  L.t2 = take(T * H * eb);
+  L.du = take(T * F * eb);
+  L.dqkv = take(T * 3 * H * eb);
+  L.delta = take((size_t)d->batch * d->heads * d->seq * 4);
+  L.part_row = take((size_t)bdrln_bwd_blocks((int64_t)T) * 3 * H * 4);
+  const size_t widest = F > 3 * H ? F : 3 * H;
+  L.part_col = take((size_t)colsum_blocks((int64_t)T) * widest * 4);
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* slapo_status_string(int status) {
+  switch (status) {
+    case SLAPO_OK: return "ok";
+    case SLAPO_ERR_NULL: return "a required pointer is NULL";
+    case SLAPO_ERR_SHAPE: return "invalid shape or scalar argument";
+    case SLAPO_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SLAPO_ERR_ALIGN: return "pointer not 16-byte aligned or size not a multiple of 8";
+    case SLAPO_ERR_WORKSPACE: return "workspace too small";
+    case SLAPO_ERR_HIP: return "HIP reported an error";
+    default: return "unknown status";
+  }
+}
+
+int slapo_layer_workspace(const slapo_layer_desc* desc, size_t* saved_bytes, size_t* scratch_bytes) {
+  if (!saved_bytes || !scratch_bytes) return SLAPO_ERR_NULL;
+  const int rc = check_desc(desc);
+  if (rc) return rc;
+  *saved_bytes = saved_layout(desc).total;
+  *scratch_bytes = scratch_layout(desc).total;
+  return SLAPO_OK;
+}
+
+int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, size_t* offset, size_t* bytes) {
+  if (!name || !offset || !bytes) return SLAPO_ERR_NULL;
+  const int rc = check_desc(desc);
+  if (rc) return rc;
+  const SavedLayout L = saved_layout(desc);
+  const size_t eb = desc->dtype == SLAPO_FP32 ? 4 : 2;
+  const size_t T = (size_t)desc->batch * desc->seq, H = desc->hidden, F = desc->ffn;
+  size_t off = (size_t)-1, len = 0;
+  if (!strcmp(name, "qkv")) { off = L.qkv; len = T * 3 * H * eb; }
+  else if (!strcmp(name, "attn")) { off = L.attn; len = T * H * eb; }
+  else if (!strcmp(name, "lse")) { off = L.lse; len = (size_t)desc->batch * desc->heads * desc->seq * 4; }
+  else if (!strcmp(name, "z1")) { off = L.z1; len = T * H * eb; }
+  else if (!strcmp(name, "n1")) { off = L.n1; len = T * H * eb; }
+  else if (!strcmp(name, "y1") && !desc->pre_ln) { off = L.y1; len = T * H * eb; }
+  else if (!strcmp(name, "n2") && desc->pre_ln) { off = L.y1; len = T * H * eb; }
+  else if (!strcmp(name, "u")) { off = L.u; len = T * F * eb; }
+  else if (!strcmp(name, "g")) { off = L.g; len = T * F * eb; }
+  else if (!strcmp(name, "z2")) { off = L.z2; len = T * H * eb; }
+  else if (!strcmp(name, "mu1")) { off = L.mu1; len = T * 4; }
+  else if (!strcmp(name, "rstd1")) { off = L.rstd1; len = T * 4; }
+  else if (!strcmp(name, "mu2")) { off = L.mu2; len = T * 4; }
+  else if (!strcmp(name, "rstd2")) { off = L.rstd2; len = T * 4; }
+  if (off == (size_t)-1) return SLAPO_ERR_UNSUPPORTED;
+  *offset = off;
+  *bytes = len;
+  return SLAPO_OK;
+}
+
+int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
+                    void* y, void* saved, void* scratch, void* stream) {
+  int rc = check_desc(d);
+  if (rc) return rc;
+  if (!p || !x || !y || !saved || !scratch) return SLAPO_ERR_NULL;
+  const void* ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
+  for (const void* q : ps) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
+  if (misaligned(x) || misaligned(y) || misaligned(saved) || misaligned(scratch)) return SLAPO_ERR_ALIGN;
+
+  hipStream_t st = (hipStream_t)stream;
+  const int f32 = d->dtype == SLAPO_FP32;
+  const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
+  const SavedLayout L = saved_layout(d);
+  const ScratchLayout W = scratch_layout(d);
+  char* sv = (char*)saved;
+  char* sc = (char*)scratch;
+  void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *u = sv + L.u, *g = sv + L.g;
+  float *lse = (float*)(sv + L.lse), *mu1 = (float*)(sv + L.mu1), *rstd1 = (float*)(sv + L.rstd1);
+  float *mu2 = (float*)(sv + L.mu2), *rstd2 = (float*)(sv + L.rstd2);
+  void* r = sc + W.t0;
+  const AttnShape as = {d->batch, d->seq, H, d->heads, d->causal};
+  const DropoutParams dp0 = make_dropout(d, 0), dp1 = make_dropout(d, 1);
+
+  const void* attn_in = x;
+  if (d->pre_ln) {
+    void* n1 = sv + L.n1;
+    launch_bdrln_fwd(f32, T, H, nullptr, nullptr, x, p->ln1_g, p->ln1_b, nullptr, n1, mu1, rstd1, dp0, d->ln_eps, st);
+    attn_in = n1;
+  }
+  launch_gemm(f32, GEMM_NT, EPI_BIAS, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
+  launch_attn_fwd(f32, as, qkv, seqlens, attn, lse, st);
+  launch_gemm(f32, GEMM_NT, EPI_NONE, d->act, T, H, H, attn, p->wo, r, nullptr, nullptr, nullptr, st);
+  if (d->pre_ln) launch_bdrln_fwd(f32, T, H, r, p->bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, st);
+  else launch_bdrln_fwd(f32, T, H, r, p->bo, x, p->ln1_g, p->ln1_b, z1, y1, mu1, rstd1, dp0, d->ln_eps, st);
+  launch_gemm(f32, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st);
+  launch_gemm(f32, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st);
+  if (d->pre_ln) {
+    launch_bdrln_fwd(f32, T, H, r, p->b2, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, dp1, d->ln_eps, st);
+  } else {
+    void* z2 = sv + L.z2;
+    launch_bdrln_fwd(f32, T, H, r, p->b2, y1, p->ln2_g, p->ln2_b, z2, y, mu2, rstd2, dp1, d->ln_eps, st);
+  }
+  return finish();
+}
+
+int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
+                    const void* dy, const void* saved, void* dx, const slapo_layer_grads* gr, void* scratch,
+                    void* stream) {
+  int rc = check_desc(d);
+  if (rc) return rc;
+  if (!p || !x || !dy || !saved || !dx || !gr || !scratch) return SLAPO_ERR_NULL;
+  const void* ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
+  const void* gs[12] = {gr->wqkv, gr->bqkv, gr->wo, gr->bo, gr->ln1_g, gr->ln1_b, gr->w1, gr->b1, gr->w2, gr->b2, gr->ln2_g, gr->ln2_b};
+  for (const void* q : ps) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
+  for (const void* q : gs) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
+  if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(saved) || misaligned(scratch)) return SLAPO_ERR_ALIGN;
+
+  hipStream_t st = (hipStream_t)stream;
+  const int f32 = d->dtype == SLAPO_FP32, acc = d->accumulate_grads ? 1 : 0;
+  const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
+  const SavedLayout L = saved_layout(d);
+  const ScratchLayout W = scratch_layout(d);
+  const char* sv = (const char*)saved;
+  char* sc = (char*)scratch;
+  const void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *u = sv + L.u, *g = sv + L.g;
+  const float *lse = (const float*)(sv + L.lse), *mu1 = (const float*)(sv + L.mu1), *rstd1 = (const float*)(sv + L.rstd1);
+  const float *mu2 = (const float*)(sv + L.mu2), *rstd2 = (const float*)(sv + L.rstd2);
+  void *t0 = sc + W.t0, *t1 = sc + W.t1, *t2 = sc + W.t2, *du = sc + W.du, *dqkv = sc + W.dqkv;
+  float *delta = (float*)(sc + W.delta), *prow = (float*)(sc + W.part_row), *pcol = (float*)(sc + W.part_col);
+  const AttnShape as = {d->batch, d->seq, H, d->heads, d->causal};
+  const DropoutParams dp0 = make_dropout(d, 0), dp1 = make_dropout(d, 1);
+  const int nrow = bdrln_bwd_blocks(T), ncol = colsum_blocks(T);
+  // weight gradient: C (+)= A^T B
+  auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
+    launch_gemm(f32, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, st);
+  };
+  auto reduce_rows = [&](int which, void* out) {
+    launch_colreduce_partials(f32, nrow, 3 * (int64_t)H, H, prow + (size_t)which * H, out, acc, st);
+  };
+  auto colsum = [&](const void* a, int N, void* out) {
+    launch_colsum_partials(f32, T, N, a, pcol, st);
+    launch_colreduce_partials(f32, ncol, N, N, pcol, out, acc, st);
+  };
+
+  // ---- FFN block ----
+  if (d->pre_ln) {
+    launch_bdrln_bwd(f32, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, st);
+  } else {
+    launch_bdrln_bwd(f32, T, H, dy, sv + L.z2, mu2, rstd2, p->ln2_g, nullptr, t0, t1, prow, dp1, st);
+    reduce_rows(0, gr->ln2_g);
+    reduce_rows(1, gr->ln2_b);
+  }
+  reduce_rows(2, gr->b2);
+  launch_gemm(f32, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+  dweight(H, F, t1, g, gr->w2);
+  colsum(du, F, gr->b1);
+  dweight(F, H, du, y1, gr->w1);
+  if (d->pre_ln) launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
+  else launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
+  // ---- attention block ----
+  if (d->pre_ln) {
+    launch_bdrln_bwd(f32, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t1, prow, dp0, st);
+    reduce_rows(0, gr->ln2_g);
+    reduce_rows(1, gr->ln2_b);
+  } else {
+    launch_bdrln_bwd(f32, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t1, prow, dp0, st);
+    reduce_rows(0, gr->ln1_g);
+    reduce_rows(1, gr->ln1_b);
+  }
+  reduce_rows(2, gr->bo);
+  launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, H, t1, p->wo, t0, nullptr, nullptr, nullptr, st);
+  dweight(H, H, t1, attn, gr->wo);
+  launch_attn_bwd(f32, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
+  colsum(dqkv, 3 * H, gr->bqkv);
+  if (d->pre_ln) {
+    dweight(3 * H, H, dqkv, sv + L.n1, gr->wqkv);
+    launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, 3 * H, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
+    launch_bdrln_bwd(f32, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, st);
+    reduce_rows(0, gr->ln1_g);
+    reduce_rows(1, gr->ln1_b);
+  } else {
+    dweight(3 * H, H, dqkv, x, gr->wqkv);
+    launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
+  }
+  return finish();
+}
+
+int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
+               const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_ADD) return SLAPO_ERR_UNSUPPORTED;
+  if (act != SLAPO_GELU_ERF && act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
+  if (M <= 0 || N <= 0 || K <= 0) return SLAPO_ERR_SHAPE;
+  if (M * N >= ((int64_t)1 << 31) || M * K >= ((int64_t)1 << 31) || N * K >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  if (!A || !B || !C) return SLAPO_ERR_NULL;
+  if ((epilogue == EPI_BIAS || epilogue == EPI_BIAS_ACT) && !bias) return SLAPO_ERR_NULL;
+  if (epilogue == EPI_BIAS_ACT && !aux_out) return SLAPO_ERR_NULL;
+  if ((epilogue == EPI_DACT || epilogue == EPI_ADD) && !aux_in) return SLAPO_ERR_NULL;
+  if (N % 8) return SLAPO_ERR_ALIGN;
+  if (layout == GEMM_TN ? (M % 8) : (K % 8)) return SLAPO_ERR_ALIGN;   // A's contiguous dimension
+  if (layout == GEMM_NT && (K % 8)) return SLAPO_ERR_ALIGN;
+  if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
+  launch_gemm(dtype == SLAPO_FP32, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
+              (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_attn_fwd(const slapo_layer_desc* d, const void* qkv, const int32_t* seqlens, void* out, float* lse,
+                   void* stream) {
+  const int rc = check_desc(d);
+  if (rc) return rc;
+  if (!qkv || !out || !lse) return SLAPO_ERR_NULL;
+  if (misaligned(qkv) || misaligned(out)) return SLAPO_ERR_ALIGN;
+  const AttnShape as = {d->batch, d->seq, d->hidden, d->heads, d->causal};
+  launch_attn_fwd(d->dtype == SLAPO_FP32, as, qkv, seqlens, out, lse, (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_attn_bwd(const slapo_layer_desc* d, const void* qkv, const int32_t* seqlens, const void* out,
+                   const void* dout, const float* lse, float* delta, void* dqkv, void* stream) {
+  const int rc = check_desc(d);
+  if (rc) return rc;
+  if (!qkv || !out || !dout || !lse || !delta || !dqkv) return SLAPO_ERR_NULL;
+  if (misaligned(qkv) || misaligned(out) || misaligned(dout) || misaligned(dqkv)) return SLAPO_ERR_ALIGN;
+  const AttnShape as = {d->batch, d->seq, d->hidden, d->heads, d->causal};
+  launch_attn_bwd(d->dtype == SLAPO_FP32, as, qkv, seqlens, out, dout, lse, delta, dqkv, (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_bdrln_fwd(const slapo_layer_desc* d, int site, int64_t T, const void* r, const void* bias, const void* res,
+                    const void* gamma, const void* beta, void* z_out, void* out, float* mu, float* rstd,
+                    void* stream) {
+  const int rc = check_desc(d);
+  if (rc) return rc;
+  if (T <= 0 || site < 0 || site > 1) return SLAPO_ERR_SHAPE;
+  if (!res) return SLAPO_ERR_NULL;
+  if (r && (!bias || !z_out)) return SLAPO_ERR_NULL;
+  if (gamma && (!beta || !out || !mu || !rstd)) return SLAPO_ERR_NULL;
+  if (!r && !gamma) return SLAPO_ERR_NULL;
+  if (misaligned(r) || misaligned(bias) || misaligned(res) || misaligned(gamma) || misaligned(beta) ||
+      misaligned(z_out) || misaligned(out)) return SLAPO_ERR_ALIGN;
+  launch_bdrln_fwd(d->dtype == SLAPO_FP32, T, d->hidden, r, bias, res, gamma, beta, z_out, out, mu, rstd,
+                   make_dropout(d, site), d->ln_eps, (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_bdrln_bwd_blocks(int64_t T) { return bdrln_bwd_blocks(T); }
+
+int slapo_bdrln_bwd(const slapo_layer_desc* d, int site, int64_t T, const void* dout, const void* z, const float* mu,
+                    const float* rstd, const void* gamma, const void* dres_in, void* dz_out, void* dr_out,
+                    float* partials, void* stream) {
+  const int rc = check_desc(d);
+  if (rc) return rc;
+  if (T <= 0 || site < 0 || site > 1) return SLAPO_ERR_SHAPE;
+  if (!dout || !partials) return SLAPO_ERR_NULL;
+  if (gamma && (!z || !mu || !rstd)) return SLAPO_ERR_NULL;
+  if (!dz_out && !dr_out) return SLAPO_ERR_NULL;
+  if (misaligned(dout) || misaligned(z) || misaligned(gamma) || misaligned(dres_in) || misaligned(dz_out) ||
+      misaligned(dr_out) || misaligned(partials)) return SLAPO_ERR_ALIGN;
+  launch_bdrln_bwd(d->dtype == SLAPO_FP32, T, d->hidden, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials,
+                   make_dropout(d, site), (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_colsum_blocks(int64_t T) { return colsum_blocks(T); }
+
+int slapo_colsum_partials(int dtype, int64_t T, int64_t N, const void* a, float* partials, void* stream) {
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (T <= 0 || N <= 0) return SLAPO_ERR_SHAPE;
+  if (!a || !partials) return SLAPO_ERR_NULL;
+  if (N % 8 || misaligned(a) || misaligned(partials)) return SLAPO_ERR_ALIGN;
+  launch_colsum_partials(dtype == SLAPO_FP32, T, N, a, partials, (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_colreduce_partials(int dtype, int64_t nblk, int64_t stride, int64_t N, const float* partials, void* out,
+                             int accumulate, void* stream) {
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (nblk <= 0 || N <= 0 || stride < N) return SLAPO_ERR_SHAPE;
+  if (!partials || !out) return SLAPO_ERR_NULL;
+  launch_colreduce_partials(dtype == SLAPO_FP32, nblk, stride, N, partials, out, accumulate, (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_dropout_mask(const slapo_layer_desc* d, int site, int64_t T, uint8_t* mask, void* stream) {
+  const int rc = check_desc(d);
+  if (rc) return rc;
+  if (T <= 0 || site < 0 || site > 1) return SLAPO_ERR_SHAPE;
+  if (!mask) return SLAPO_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(mask) & 7u) != 0) return SLAPO_ERR_ALIGN;
+  launch_dropout_mask(T * d->hidden, mask, make_dropout(d, site), (hipStream_t)stream);
+  return finish();
+}
+
+}  // extern "C"

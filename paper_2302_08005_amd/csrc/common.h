@@ -1,0 +1,98 @@
+// Shared device helpers for the gfx950 kernels: bf16 packing, 16-byte vector access, wave
+// reductions and the Philox4x32-10 dropout draw.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace slapo {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+typedef uint16_t bf16_t;  // storage type of a bf16 element
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// round-to-nearest-even pack of two floats into one dword (lo = a, hi = b)
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  f32x2_t v = {a, b};
+  bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+  return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ bf16_t f32_to_bf16(float a) { return (bf16_t)(pack_bf16x2(a, 0.f) & 0xffffu); }
+
+// Eight consecutive elements of either storage type <-> eight floats.
+__device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
+  uint4 w = *reinterpret_cast<const uint4*>(p);
+  v[0] = bf16lo_to_f32(w.x); v[1] = bf16hi_to_f32(w.x); v[2] = bf16lo_to_f32(w.y); v[3] = bf16hi_to_f32(w.y);
+  v[4] = bf16lo_to_f32(w.z); v[5] = bf16hi_to_f32(w.z); v[6] = bf16lo_to_f32(w.w); v[7] = bf16hi_to_f32(w.w);
+}
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
+  uint4 w;
+  w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
+  w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
+  *reinterpret_cast<uint4*>(p) = w;
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ float to_f32(bf16_t h) { return bf16_to_f32(h); }
+__device__ __forceinline__ float to_f32(float f) { return f; }
+__device__ __forceinline__ void from_f32(bf16_t& d, float f) { d = f32_to_bf16(f); }
+__device__ __forceinline__ void from_f32(float& d, float f) { d = f; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Philox4x32-10 block function (Salmon et al., SC'11): counter c[4], key k[2].
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&o)[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
+}
+
+struct DropoutParams {
+  uint32_t key0, key1;   // low / high half of the seed
+  uint32_t site, layer;  // third and fourth counter word
+  uint32_t thr;          // keep iff 16-bit draw >= thr
+  float scale;           // 1 / (1 - p)
+};
+
+// Keep decisions of the eight elements of block `blk` (= element index >> 3), bit j = element j kept.
+__device__ __forceinline__ uint32_t dropout_keep8(const DropoutParams& dp, uint64_t blk) {
+  uint32_t o[4];
+  philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), dp.site, dp.layer, dp.key0, dp.key1, o);
+  uint32_t bits = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t r16 = (o[j >> 1] >> (16 * (j & 1))) & 0xffffu;
+    bits |= (r16 >= dp.thr ? 1u : 0u) << j;
+  }
+  return bits;
+}
+
+}  // namespace slapo

@@ -1,0 +1,351 @@
+// HBM-bound row kernels: the fused bias + dropout + residual + LayerNorm pattern of the scheduled
+// layer (paper section 2.2 and the appendix schedule's "LNResidual" fusion), its hand-derived
+// backward, and the deterministic two-stage column reductions for bias / gamma / beta gradients.
+//
+// One wavefront owns one row of H elements at a time: lane l holds the 8-element chunks l, l+64, ...
+// of the row in registers, so every tensor is read and written exactly once with 16-byte accesses
+// and the row statistics are plain 64-lane reductions. The dropout decision of a chunk comes from
+// one Philox4x32-10 call on the chunk's index, so nothing about the mask is ever stored.
+#include "common.h"
+#include "kernels.h"
+
+namespace slapo {
+
+template <typename T, int NCH, bool BDR, bool LN, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void bdrln_fwd_kernel(
+    int64_t rows, int H, const T* __restrict__ r, const T* __restrict__ bias, const T* __restrict__ res,
+    const T* __restrict__ gamma, const T* __restrict__ beta, T* __restrict__ z_out, T* __restrict__ out,
+    float* __restrict__ mu_out, float* __restrict__ rstd_out, DropoutParams dp, float eps) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nchunk = H >> 3;
+  const float inv_h = 1.0f / (float)H;
+  for (int64_t row = (int64_t)blockIdx.x * WAVES + wave; row < rows; row += (int64_t)gridDim.x * WAVES) {
+    const int64_t base = row * H;
+    float v[NCH][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        load8(res + base + c * 8, v[i]);
+        if (BDR) {
+          float a[8], b[8];
+          load8(r + base + c * 8, a);
+          load8(bias + c * 8, b);
+          const uint32_t keep = dropout_keep8(dp, (uint64_t)(base >> 3) + (uint64_t)c);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float t = (a[j] + b[j]) * dp.scale;
+            v[i][j] += ((keep >> j) & 1u) ? t : 0.f;
+          }
+          if (z_out) {
+            store8(z_out + base + c * 8, v[i]);
+            if (LN && sizeof(T) == 2) {
+              // statistics are taken of the stored (rounded) sum, the value backward will read
+#pragma unroll
+              for (int j = 0; j < 8; ++j) v[i][j] = bf16_to_f32(f32_to_bf16(v[i][j]));
+            }
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sum += v[i][j];
+      }
+    }
+    if (!LN) continue;
+    const float mean = wave_sum(sum) * inv_h;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      if (lane + 64 * i < nchunk) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { const float d = v[i][j] - mean; sq += d * d; }
+      }
+    }
+    const float rstd = rsqrtf(wave_sum(sq) * inv_h + eps);
+    if (lane == 0) { mu_out[row] = mean; rstd_out[row] = rstd; }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        float g[8], b[8], y[8];
+        load8(gamma + c * 8, g);
+        load8(beta + c * 8, b);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) y[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
+        store8(out + base + c * 8, y);
+      }
+    }
+  }
+}
+
+// Backward of out = LN(z), z = res + keep*(r+bias)*scale.  See slapo_bdrln_bwd for the contract.
+template <typename T, int NCH, bool LN, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
+    int64_t rows, int H, const T* __restrict__ dout, const T* __restrict__ z, const float* __restrict__ mu,
+    const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres_in,
+    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp) {
+  extern __shared__ float red[];  // [WAVES/2][3][H]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nchunk = H >> 3;
+  const float inv_h = 1.0f / (float)H;
+  float pg[NCH][8], pb[NCH][8], pd[NCH][8];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pg[i][j] = pb[i][j] = pd[i][j] = 0.f;
+
+  for (int64_t row = (int64_t)blockIdx.x * WAVES + wave; row < rows; row += (int64_t)gridDim.x * WAVES) {
+    const int64_t base = row * H;
+    float dy[NCH][8], xh[NCH][8];
+    float s1 = 0.f, s2 = 0.f, m = 0.f, rs = 0.f;
+    if (LN) { m = mu[row]; rs = rstd[row]; }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        load8(dout + base + c * 8, dy[i]);
+        if (LN) {
+          float zz[8], g[8];
+          load8(z + base + c * 8, zz);
+          load8(gamma + c * 8, g);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            xh[i][j] = (zz[j] - m) * rs;
+            pg[i][j] += dy[i][j] * xh[i][j];
+            pb[i][j] += dy[i][j];
+            dy[i][j] *= g[j];  // from here on dy holds g = dout * gamma
+            s1 += dy[i][j];
+            s2 += dy[i][j] * xh[i][j];
+          }
+        }
+      }
+    }
+    if (LN) { s1 = wave_sum(s1) * inv_h; s2 = wave_sum(s2) * inv_h; }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        float dz[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dz[j] = LN ? rs * (dy[i][j] - s1 - xh[i][j] * s2) : dy[i][j];
+        if (dres_in) {
+          float e[8];
+          load8(dres_in + base + c * 8, e);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dz[j] += e[j];
+        }
+        if (dz_out) store8(dz_out + base + c * 8, dz);
+        if (dr_out) {
+          const uint32_t keep = dropout_keep8(dp, (uint64_t)(base >> 3) + (uint64_t)c);
+          float dr[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            dr[j] = ((keep >> j) & 1u) ? dz[j] * dp.scale : 0.f;
+            pd[i][j] += dr[j];
+          }
+          store8(dr_out + base + c * 8, dr);
+        }
+      }
+    }
+  }
+  // fixed-order tree over the waves of the block, then one partial row per block
+  for (int s = WAVES / 2; s >= 1; s >>= 1) {
+    if (wave >= s && wave < 2 * s) {
+      float* slot = red + (size_t)(wave - s) * 3 * H;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nchunk) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            slot[c * 8 + j] = pg[i][j]; slot[H + c * 8 + j] = pb[i][j]; slot[2 * H + c * 8 + j] = pd[i][j];
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (wave < s) {
+      const float* slot = red + (size_t)wave * 3 * H;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nchunk) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            pg[i][j] += slot[c * 8 + j]; pb[i][j] += slot[H + c * 8 + j]; pd[i][j] += slot[2 * H + c * 8 + j];
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+    float* prow = partials + (size_t)blockIdx.x * 3 * H;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        store8(prow + c * 8, pg[i]);
+        store8(prow + H + c * 8, pb[i]);
+        store8(prow + 2 * H + c * 8, pd[i]);
+      }
+    }
+  }
+}
+
+// stage 1 of a column sum: block (bx, by) sums rows of slab by for the 32 chunks of column group bx
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partials_kernel(int64_t rows, int64_t N, const T* __restrict__ a,
+                                                              float* __restrict__ partials) {
+  __shared__ float red[8][32][8];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int64_t chunk = (int64_t)blockIdx.x * 32 + cx;
+  const int64_t per = (rows + gridDim.y - 1) / gridDim.y;
+  const int64_t r0 = (int64_t)blockIdx.y * per, r1 = (r0 + per < rows) ? r0 + per : rows;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (chunk * 8 < N) {
+    for (int64_t rr = r0 + ry; rr < r1; rr += 8) {
+      float v[8];
+      load8(a + rr * N + chunk * 8, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += v[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) red[ry][cx][j] = acc[j];
+  __syncthreads();
+  if (ry == 0 && chunk * 8 < N) {
+#pragma unroll
+    for (int k = 1; k < 8; ++k)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += red[k][cx][j];
+    store8(partials + (int64_t)blockIdx.y * N + chunk * 8, acc);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void colreduce_partials_kernel(int64_t nblk, int64_t stride, int64_t N,
+                                                                 const float* __restrict__ partials,
+                                                                 T* __restrict__ out, int accumulate) {
+  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float s = 0.f;
+  for (int64_t i = 0; i < nblk; ++i) s += partials[i * stride + n];
+  if (accumulate) s += to_f32(out[n]);
+  from_f32(out[n], s);
+}
+
+__global__ __launch_bounds__(256) void dropout_mask_kernel(int64_t nblocks8, uint8_t* __restrict__ mask,
+                                                           DropoutParams dp) {
+  const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (b >= nblocks8) return;
+  const uint32_t keep = dropout_keep8(dp, (uint64_t)b);
+  uint2 w;
+  w.x = (keep & 1u) | ((keep >> 1 & 1u) << 8) | ((keep >> 2 & 1u) << 16) | ((keep >> 3 & 1u) << 24);
+  w.y = (keep >> 4 & 1u) | ((keep >> 5 & 1u) << 8) | ((keep >> 6 & 1u) << 16) | ((keep >> 7 & 1u) << 24);
+  *reinterpret_cast<uint2*>(mask + b * 8) = w;
+}
+
+// ---- host launchers -----------------------------------------------------------------------------
+
+static int nch_for(int H) { const int n = (H / 8 + 63) / 64; return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : n <= 5 ? 5 : 8; }
+
+template <typename T, bool BDR, bool LN>
+static void launch_fwd(int64_t rows, int H, const void* r, const void* bias, const void* res, const void* gamma,
+                       const void* beta, void* z_out, void* out, float* mu, float* rstd, const DropoutParams& dp,
+                       float eps, hipStream_t st) {
+  constexpr int WAVES = 4;
+  int64_t blocks = (rows + WAVES - 1) / WAVES;
+  if (blocks > 4096) blocks = 4096;
+#define SLAPO_FWD(N)                                                                                          \
+  hipLaunchKernelGGL((bdrln_fwd_kernel<T, N, BDR, LN, WAVES>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, st, \
+                     rows, H, (const T*)r, (const T*)bias, (const T*)res, (const T*)gamma, (const T*)beta,    \
+                     (T*)z_out, (T*)out, mu, rstd, dp, eps)
+  switch (nch_for(H)) {
+    case 1: SLAPO_FWD(1); break;
+    case 2: SLAPO_FWD(2); break;
+    case 4: SLAPO_FWD(4); break;
+    case 5: SLAPO_FWD(5); break;
+    default: SLAPO_FWD(8); break;
+  }
+#undef SLAPO_FWD
+}
+
+void launch_bdrln_fwd(int dtype_fp32, int64_t rows, int H, const void* r, const void* bias, const void* res,
+                      const void* gamma, const void* beta, void* z_out, void* out, float* mu, float* rstd,
+                      const DropoutParams& dp, float eps, hipStream_t st) {
+  const bool bdr = r != nullptr, ln = gamma != nullptr;
+#define SLAPO_PICK(T)                                                                                   \
+  if (bdr && ln) launch_fwd<T, true, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st); \
+  else if (bdr) launch_fwd<T, true, false>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st); \
+  else launch_fwd<T, false, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st)
+  if (dtype_fp32) { SLAPO_PICK(float); } else { SLAPO_PICK(bf16_t); }
+#undef SLAPO_PICK
+}
+
+int bdrln_bwd_blocks(int64_t rows) {
+  int64_t b = (rows + 7) / 8;
+  return (int)(b > 256 ? 256 : (b < 1 ? 1 : b));
+}
+
+template <typename T, bool LN>
+static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, const float* mu, const float* rstd,
+                       const void* gamma, const void* dres_in, void* dz_out, void* dr_out, float* partials,
+                       const DropoutParams& dp, hipStream_t st) {
+  const int blocks = bdrln_bwd_blocks(rows);
+#define SLAPO_BWD(N, W)                                                                                      \
+  do {                                                                                                       \
+    auto kern = bdrln_bwd_kernel<T, N, LN, W>;                                                               \
+    const size_t lds = (size_t)(W / 2) * 3 * H * 4;                                                          \
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(W * 64), lds, st, rows, H, (const T*)dout, (const T*)z, mu,  \
+                       rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp);      \
+  } while (0)
+  switch (nch_for(H)) {
+    case 1: SLAPO_BWD(1, 8); break;
+    case 2: SLAPO_BWD(2, 8); break;
+    case 4: SLAPO_BWD(4, 8); break;
+    case 5: SLAPO_BWD(5, 4); break;
+    default: SLAPO_BWD(8, 4); break;
+  }
+#undef SLAPO_BWD
+}
+
+void launch_bdrln_bwd(int dtype_fp32, int64_t rows, int H, const void* dout, const void* z, const float* mu,
+                      const float* rstd, const void* gamma, const void* dres_in, void* dz_out, void* dr_out,
+                      float* partials, const DropoutParams& dp, hipStream_t st) {
+  const bool ln = gamma != nullptr;
+  if (dtype_fp32) {
+    if (ln) launch_bwd<float, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
+    else launch_bwd<float, false>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
+  } else {
+    if (ln) launch_bwd<bf16_t, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
+    else launch_bwd<bf16_t, false>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
+  }
+}
+
+int colsum_blocks(int64_t rows) {
+  int64_t b = (rows + 31) / 32;
+  return (int)(b > 64 ? 64 : (b < 1 ? 1 : b));
+}
+
+void launch_colsum_partials(int dtype_fp32, int64_t rows, int64_t N, const void* a, float* partials,
+                            hipStream_t st) {
+  dim3 grid((unsigned)((N / 8 + 31) / 32), (unsigned)colsum_blocks(rows));
+  if (dtype_fp32) hipLaunchKernelGGL(colsum_partials_kernel<float>, grid, dim3(256), 0, st, rows, N, (const float*)a, partials);
+  else hipLaunchKernelGGL(colsum_partials_kernel<bf16_t>, grid, dim3(256), 0, st, rows, N, (const bf16_t*)a, partials);
+}
+
+void launch_colreduce_partials(int dtype_fp32, int64_t nblk, int64_t stride, int64_t N, const float* partials,
+                               void* out, int accumulate, hipStream_t st) {
+  dim3 grid((unsigned)((N + 255) / 256));
+  if (dtype_fp32) hipLaunchKernelGGL(colreduce_partials_kernel<float>, grid, dim3(256), 0, st, nblk, stride, N, partials, (float*)out, accumulate);
+  else hipLaunchKernelGGL(colreduce_partials_kernel<bf16_t>, grid, dim3(256), 0, st, nblk, stride, N, partials, (bf16_t*)out, accumulate);
+}
+
+void launch_dropout_mask(int64_t n_elements, uint8_t* mask, const DropoutParams& dp, hipStream_t st) {
+  const int64_t nb = n_elements / 8;
+  hipLaunchKernelGGL(dropout_mask_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, nb, mask, dp);
+}
+
+}  // namespace slapo

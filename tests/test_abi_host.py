@@ -1,0 +1,69 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header declares, and rejects
+bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2302_08005_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "slapo.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(slapo_[a-z0-9_]+)\s*\(", header))
+    assert {"slapo_layer_fwd", "slapo_layer_bwd", "slapo_layer_workspace", "slapo_gemm", "slapo_attn_fwd",
+            "slapo_attn_bwd", "slapo_bdrln_fwd", "slapo_bdrln_bwd", "slapo_dropout_mask"} <= names
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_descriptor_validation():
+    ok = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024)
+    saved, scratch = B.slapo_layer_workspace(ok)
+    assert saved > 0 and scratch > 0
+    bad = [
+        (dict(heads=5), -2), (dict(batch=0), -2), (dict(dropout_p=1.0), -2), (dict(dropout_p=-0.1), -2),
+        (dict(hidden=256, heads=8), -3), (dict(hidden=8192, heads=64), -3), (dict(dtype=7), -3), (dict(act=3), -3),
+        (dict(ffn=1001), -4), (dict(ln_eps=0.0), -2),
+    ]
+    for kw, code in bad:
+        base = dict(batch=2, seq=128, hidden=256, heads=4, ffn=1024)
+        base.update(kw)
+        with pytest.raises(B.SlapoError) as e:
+            B.slapo_layer_workspace(B.make_desc(**base))
+        assert e.value.status == code, (kw, e.value.status)
+
+
+def test_null_and_alignment_errors_come_before_any_device_work():
+    d = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024)
+    lib = B.lib()
+    params = B._Ptrs(**{n: 4096 for n in B.PARAM_NAMES})
+    assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), None, None, 4096, 4096, 4096, None) == -1
+    assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), 4096 + 4, None, 4096, 4096, 4096, None) == -4
+    params.wo = None
+    assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), 4096, None, 4096, 4096, 4096, None) == -1
+    assert lib.slapo_gemm(0, 0, 0, 0, 128, 128, 0, 4096, 4096, 4096, None, None, None, None) == -2
+    assert lib.slapo_gemm(0, 0, 1, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -1
+    assert lib.slapo_gemm(0, 0, 0, 0, 128, 132, 64, 4096, 4096, 4096, None, None, None, None) == -4
+    assert lib.slapo_gemm(0, 5, 0, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -3
+    assert lib.slapo_dropout_mask(C.byref(d), 2, 256, 4096, None) == -2
+    assert B.status_string(-6).startswith("HIP")
+
+
+def test_saved_regions_are_disjoint_and_inside_the_buffer():
+    for pre_ln in (0, 1):
+        d = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024, pre_ln=pre_ln)
+        saved, _ = B.slapo_layer_workspace(d)
+        names = ["qkv", "attn", "lse", "z1", "u", "g", "mu1", "rstd1", "mu2", "rstd2"]
+        names += ["n1", "n2"] if pre_ln else ["y1", "z2"]
+        spans = sorted(B.slapo_layer_saved_region(d, n) for n in names)
+        for (o0, b0), (o1, _) in zip(spans, spans[1:]):
+            assert o0 + b0 <= o1
+        assert spans[-1][0] + spans[-1][1] <= saved
+        with pytest.raises(B.SlapoError):
+            B.slapo_layer_saved_region(d, "y1" if pre_ln else "n1")

@@ -1,0 +1,66 @@
+"""GPU parity of the GEMMs and their fused epilogues vs fp64 products of the same stored inputs."""
+import numpy as np
+import pytest
+import torch
+from scipy.special import erf
+
+import workloads as W
+from paper_2302_08005_amd import binding as B
+from gpu_util import DEV, TOL, err, store, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _act(u, act):
+    return 0.5 * u * (1 + erf(u / np.sqrt(2))) if act == W.GELU else np.maximum(u, 0)
+
+
+def _dact(u, act):
+    if act == W.RELU:
+        return (u > 0).astype(np.float64)
+    return 0.5 * (1 + erf(u / np.sqrt(2))) + u * np.exp(-0.5 * u * u) / np.sqrt(2 * np.pi)
+
+
+SHAPES = [(256, 256, 128), (296, 264, 200), (128, 128, 64), (1024, 768, 512), (520, 136, 72), (4096, 1024, 1024)]
+
+
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP32])
+@pytest.mark.parametrize("layout", [B.NT, B.NN, B.TN])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_layouts(dtype, layout, M, N, K):
+    rng = np.random.default_rng(M + 3 * N + 7 * K + layout)
+    a = store(rng.standard_normal((M, K)), dtype)
+    b = store(rng.standard_normal((K, N)) * 0.1, dtype)
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    A = to_dev(a if layout != B.TN else a.T.copy(), dtype)
+    Bm = to_dev(b.T.copy() if layout == B.NT else b, dtype)
+    Cout = torch.empty(M, N, dtype=A.dtype, device=DEV)
+    B.slapo_gemm(dtype, layout, B.EPI_NONE, 0, M, N, K, A, Bm, Cout)
+    assert err(Cout, ref) <= (5e-3 if dtype == W.BF16 else 1e-5)
+
+
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP32])
+@pytest.mark.parametrize("act", [W.GELU, W.RELU])
+def test_gemm_epilogues(dtype, act):
+    M, N, K = 392, 520, 256
+    rng = np.random.default_rng(5)
+    a = store(rng.standard_normal((M, K)), dtype)
+    w = store(rng.standard_normal((N, K)) * 0.1, dtype)
+    bias = store(rng.standard_normal(N), dtype)
+    aux = store(rng.standard_normal((M, N)), dtype)
+    acc = a.astype(np.float64) @ w.astype(np.float64).T
+    A, Wt, bd, auxd = to_dev(a, dtype), to_dev(w, dtype), to_dev(bias, dtype), to_dev(aux, dtype)
+    tol = TOL[dtype]
+    Cout = torch.empty(M, N, dtype=A.dtype, device=DEV)
+    U = torch.empty_like(Cout)
+    B.slapo_gemm(dtype, B.NT, B.EPI_BIAS, act, M, N, K, A, Wt, Cout, bias=bd)
+    assert err(Cout, acc + bias) <= tol
+    B.slapo_gemm(dtype, B.NT, B.EPI_BIAS_ACT, act, M, N, K, A, Wt, Cout, bias=bd, aux_out=U)
+    assert err(U, acc + bias) <= tol and err(Cout, _act(acc + bias, act)) <= tol
+    B.slapo_gemm(dtype, B.NT, B.EPI_DACT, act, M, N, K, A, Wt, Cout, aux_in=auxd)
+    assert err(Cout, acc * _dact(aux.astype(np.float64), act)) <= tol
+    B.slapo_gemm(dtype, B.NT, B.EPI_ADD, act, M, N, K, A, Wt, Cout, aux_in=auxd)
+    assert err(Cout, acc + aux) <= tol
+    C2 = auxd.clone()                          # in-place accumulate (aux_in aliases C)
+    B.slapo_gemm(dtype, B.NT, B.EPI_ADD, act, M, N, K, A, Wt, C2, aux_in=C2)
+    assert err(C2, acc + aux) <= tol

@@ -1,0 +1,84 @@
+"""GPU parity of the whole layer step (slapo_layer_fwd / slapo_layer_bwd) vs the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import layer as L
+from paper_2302_08005_amd import binding as B
+from gpu_util import DEV, TOL, err, to_np
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    W.CONFIGS["C1"],                                                                   # fp32 encoder, as specified
+    W.CONFIGS["C1"].replace(name="c1-bf16", dtype=W.BF16),
+    W.CONFIGS["C1"].replace(name="c1-preln-relu-causal", pre_ln=1, act=W.RELU, causal=1),
+    W.CONFIGS["C1"].replace(name="c1-bf16-preln-causal", dtype=W.BF16, pre_ln=1, causal=1),
+    W.LayerConfig("ragged-bf16", 3, 200, 384, 6, 1000, causal=0, dropout_p=0.1, dtype=W.BF16, len_lo=50, len_hi=200, config_id=11),
+    W.LayerConfig("d128-bf16-preln", 2, 264, 512, 4, 1536, causal=1, dropout_p=0.0, dtype=W.BF16, pre_ln=1, config_id=12),
+    W.LayerConfig("d128-fp32", 1, 96, 256, 2, 520, causal=1, dropout_p=0.2, dtype=W.FP32, act=W.RELU, config_id=13),
+]
+
+
+def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True):
+    params = W.make_params(cfg, perturbed=perturbed)
+    x, dy, sl = W.make_inputs(cfg, q_scale=q_scale)
+    ref = L.layer_forward(cfg, params, x, sl)
+    gref = L.layer_backward(cfg, params, ref, dy)
+    layer = B.Layer(cfg, params)
+    xd, dyd = layer.to_device(x), layer.to_device(dy)
+    sld = None if sl is None else torch.from_numpy(sl).to(DEV)
+    y = layer.forward(xd, sld)
+    dx = layer.backward(xd, sld, dyd)
+    torch.cuda.synchronize()
+    errs = {"y": err(y, ref["y"]), "dx": err(dx, gref["dx"])}
+    for k in W.PARAM_NAMES:
+        errs["d" + k] = err(layer.grads[k], gref[k])
+    if check_saved:
+        names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "u": "U", "g": "G", "lse": "LSE"}
+        names.update({"n1": "N1", "n2": "N2"} if cfg.pre_ln else {"y1": "Y1", "z2": "Z2"})
+        for k, rk in names.items():
+            errs["saved." + k] = err(layer.saved_tensor(k).reshape(-1), ref[rk].reshape(-1))
+    return errs, layer, (xd, sld, dyd, y, dx)
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_layer_parity_small(cfg):
+    errs, _, _ = run_case(cfg)
+    tol = TOL[cfg.dtype]
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
+
+
+def test_layer_is_deterministic_and_accumulates():
+    cfg = SMALL[4]
+    errs, layer, (xd, sld, dyd, y, dx) = run_case(cfg, check_saved=False)
+    g1 = {k: v.clone() for k, v in layer.grads.items()}
+    y2 = layer.forward(xd, sld)
+    dx2 = layer.backward(xd, sld, dyd)
+    assert torch.equal(y, y2) and torch.equal(dx, dx2)
+    for k in W.PARAM_NAMES:
+        assert torch.equal(g1[k], layer.grads[k]), k
+    layer.desc.accumulate_grads = 1
+    layer.backward(xd, sld, dyd)
+    for k in W.PARAM_NAMES:
+        assert err(layer.grads[k], 2 * to_np(g1[k])) <= 1e-2, k
+
+
+def test_zero_dropout_matches_layer_without_dropout_bitwise():
+    cfg = SMALL[3].replace(dropout_p=0.0)
+    _, layer, (xd, sld, dyd, y, dx) = run_case(cfg, check_saved=False)
+    layer.desc.seed = 12345          # with p = 0 the seed must not matter
+    y2 = layer.forward(xd, sld)
+    assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("key", ["C2", "C3", "C4"])
+def test_layer_parity_full_size(key):
+    """The benchmark shapes themselves, in the launch configuration bench.py times."""
+    cfg = W.CONFIGS[key]
+    errs, _, _ = run_case(cfg, perturbed=False, check_saved=False)
+    tol = TOL[cfg.dtype]
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
