@@ -1,0 +1,212 @@
+"""Benchmark of the layer training step (forward + backward) on one MI355X.
+
+One "step" = slapo_layer_fwd + slapo_layer_bwd over one synthetic batch that already sits in HBM.
+Prints ONE JSON line: whole-job samples/s plus the roofline record of the dominant kernel (measured
+live with HIP events on the launch stream) and the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+import workloads as W
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def layer_flops(cfg, seqlens):
+    """Algorithmic FLOPs of one layer forward+backward: 3 x GEMM + 3.5 x visible attention."""
+    T, H, F, S = cfg.tokens, cfg.hidden, cfg.ffn, cfg.seq
+    gemm_fwd = 2.0 * T * (4.0 * H * H + 2.0 * H * F)
+    lens = [S] * cfg.batch if seqlens is None else [int(v) for v in seqlens]
+    phi = 0.5 * (1.0 + 1.0 / S) if cfg.causal else 1.0
+    att_fwd = sum(4.0 * H * S * l * phi for l in lens)
+    return 3.0 * gemm_fwd + 3.5 * att_fwd, gemm_fwd, att_fwd
+
+
+def event_time_ms(fn, iters, stream):
+    """Average duration of fn() over `iters` launches, HIP events recorded on the launch stream."""
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(iters):
+        fn()
+    e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline(cfg, params, x, dy, seqlens):
+    """The fp64 oracle, as it stands, on the host cores: one full layer forward+backward."""
+    from oracle import layer as L
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    c = L.layer_forward(cfg, params, x, seqlens)
+    L.layer_backward(cfg, params, c, dy)
+    dt = time.perf_counter() - t0
+    return {"value": cfg.batch / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one full {cfg.name} layer forward+backward (batch {cfg.batch}), 1 repetition, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is design-only.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2302_08005_amd import binding as B
+
+    cfg = W.CONFIGS[args.config]
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    params = W.make_params(cfg)
+    x, dy, seqlens = W.make_inputs(cfg)
+    layer = B.Layer(cfg, params)
+    xd, dyd = layer.to_device(x), layer.to_device(dy)
+    sld = None if seqlens is None else torch.from_numpy(seqlens).cuda()
+    y = torch.empty_like(xd)
+    dx = torch.empty_like(xd)
+
+    def step():
+        B.slapo_layer_fwd(layer.desc, layer.params, xd, sld, y, layer.saved, layer.scratch)
+        B.slapo_layer_bwd(layer.desc, layer.params, xd, sld, dyd, layer.saved, dx, layer.grads, layer.scratch)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    gpu_ms = e0.elapsed_time(e1) / args.steps
+    ms = max(wall_ms, gpu_ms)
+
+    total_flops, gemm_fwd, att_fwd = layer_flops(cfg, seqlens)
+    T, H, F = cfg.tokens, cfg.hidden, cfg.ffn
+    dt, act = cfg.dtype, cfg.act
+
+    # dominant kernel: the FFN1 forward GEMM with the fused bias+activation epilogue, launched exactly as in
+    # the layer (same shapes, same tile selection), timed alone with events on the launch stream
+    y1 = layer.saved_tensor("n2" if cfg.pre_ln else "y1")
+    u = layer.saved_tensor("u")
+    g = torch.empty_like(u)
+
+    def ffn1():
+        B.slapo_gemm(dt, B.NT, B.EPI_BIAS_ACT, act, T, F, H, y1, layer.params["w1"], g, bias=layer.params["b1"], aux_out=u)
+
+    for _ in range(5):
+        ffn1()
+    ffn1_ms = event_time_ms(ffn1, max(20, args.steps), stream)
+    ffn1_flops = 2.0 * T * F * H
+    achieved = ffn1_flops / (ffn1_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<NT,bias+act> (FFN1 forward)", "achieved": achieved,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None, "avg_launch_us": ffn1_ms * 1e3}
+
+    # the HBM-bound fused epilogue (bias+dropout+residual+LayerNorm forward), algorithmic bytes 4*T*H*eb
+    eb = 4 if cfg.dtype == W.FP32 else 2
+    r = torch.empty_like(xd).view(T, H)
+    z = torch.empty_like(r)
+    o = torch.empty_like(r)
+    mu = torch.empty(T, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mu)
+
+    def epi():
+        B.slapo_bdrln_fwd(layer.desc, 0, T, r, layer.params["bo"], xd, layer.params["ln1_g"], layer.params["ln1_b"], z, o, mu, rstd)
+
+    r.normal_()
+    for _ in range(5):
+        epi()
+    epi_ms = event_time_ms(epi, max(20, args.steps), stream)
+    epi_gbs = 4.0 * T * H * eb / (epi_ms * 1e-3) / 1e9
+
+    extra = {"layer_tflops": total_flops / (ms * 1e-3) / 1e12,
+             "layer_frac_of_mfma_peak": total_flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+             "gpu_event_ms_per_step": gpu_ms, "wall_ms_per_step": wall_ms,
+             "epilogue_bdrln_fwd": {"bound": "hbm", "achieved": epi_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": epi_gbs / HBM_PEAK_GBS, "avg_launch_us": epi_ms * 1e3}}
+
+    if args.breakdown:
+        breakdown(cfg, layer, xd, dyd, sld, stream)
+
+    out = {"metric": "layer fwd+bwd samples/s", "value": cfg.batch / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == W.BF16 else "f32",
+           "data": "synthetic",
+           "config": {"workload": cfg.name, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
+                      "heads": cfg.heads, "ffn": cfg.ffn, "causal": cfg.causal, "dropout_p": cfg.dropout_p,
+                      "pre_ln": cfg.pre_ln, "parallelism": "single-gpu"},
+           "roofline": roofline, "extra": extra}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, params, x, dy, seqlens)
+    print(json.dumps(out), flush=True)
+
+
+def breakdown(cfg, layer, xd, dyd, sld, stream):
+    """Per-GEMM timings through the exported building blocks (diagnostics on stderr)."""
+    from paper_2302_08005_amd import binding as B
+    T, H, F = cfg.tokens, cfg.hidden, cfg.ffn
+    dt = cfg.dtype
+    dev = xd.device
+    tdt = xd.dtype
+    mk = lambda *s: torch.randn(*s, device=dev, dtype=torch.float32).to(tdt)
+    shapes = [("qkv  NT", B.NT, T, 3 * H, H), ("out  NT", B.NT, T, H, H), ("ffn1 NT", B.NT, T, F, H), ("ffn2 NT", B.NT, T, H, F),
+              ("dG   NN", B.NN, T, F, H), ("dY1  NN", B.NN, T, H, F), ("dA   NN", B.NN, T, H, H), ("dX   NN", B.NN, T, H, 3 * H),
+              ("dW2  TN", B.TN, H, F, T), ("dW1  TN", B.TN, F, H, T), ("dWo  TN", B.TN, H, H, T), ("dWqkv TN", B.TN, 3 * H, H, T)]
+    tot = 0.0
+    for name, layout, M, N, K in shapes:
+        a = mk(M, K) if layout != B.TN else mk(K, M)
+        b = mk(N, K) if layout == B.NT else mk(K, N)
+        c = torch.empty(M, N, device=dev, dtype=tdt)
+        fn = lambda: B.slapo_gemm(dt, layout, B.EPI_NONE, 0, M, N, K, a, b, c)
+        for _ in range(3):
+            fn()
+        ms = event_time_ms(fn, 20, stream)
+        tot += ms
+        print(f"  {name}: M={M} N={N} K={K}: {ms * 1e3:8.1f} us  {2.0 * M * N * K / ms / 1e9:8.1f} TFLOP/s", file=sys.stderr)
+    print(f"  GEMM total {tot * 1e3:.1f} us", file=sys.stderr)
+    desc = layer.desc
+    qkv = layer.saved_tensor("qkv")
+    attn = layer.saved_tensor("attn")
+    lse = layer.saved_tensor("lse")
+    out = torch.empty_like(attn)
+    fn = lambda: B.slapo_attn_fwd(desc, qkv, sld, out, lse)
+    fn()
+    ms = event_time_ms(fn, 20, stream)
+    print(f"  attn fwd: {ms * 1e3:8.1f} us", file=sys.stderr)
+    delta = torch.empty_like(lse)
+    dqkv = torch.empty_like(qkv)
+    fn = lambda: B.slapo_attn_bwd(desc, qkv, sld, attn, dyd, lse, delta, dqkv)
+    fn()
+    ms = event_time_ms(fn, 20, stream)
+    print(f"  attn bwd: {ms * 1e3:8.1f} us", file=sys.stderr)
+
+
+if __name__ == "__main__":
+    main()

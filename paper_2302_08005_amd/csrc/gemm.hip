@@ -178,18 +178,60 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(int M, int N, int K, con
     __syncthreads();
   }
 
-  // accumulator element r of a 32x32 tile: row (r/4)*8 + 4*(lane/32) + r%4, column lane%32
+  // Epilogue. The accumulators (element r of a 32x32 tile: row (r/4)*8 + 4*(lane/32) + r%4, column
+  // lane%32) go through a per-wave fp32 staging area in LDS so that every global access of the epilogue
+  // (bias, auxiliary input, both outputs) is a 16-byte access of 8 consecutive columns of one row.
+  // The main loop ended with a barrier, so the operand stages are free to be overwritten.
+  constexpr int LDP = WN + 4;
+  float* stage = reinterpret_cast<float*>(smem) + wave * (WM * LDP);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn0 + j * 32 + (lane & 31);
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + 4 * (lane >> 5) + (r & 3);
-        if (m < M && n < N) epilogue_store<bf16_t>(EPI, act, acc[i][j][r], m, n, N, C, bias, aux_in, aux_out);
+      for (int r = 0; r < 16; ++r)
+        stage[(i * 32 + (r >> 2) * 8 + 4 * (lane >> 5) + (r & 3)) * LDP + j * 32 + (lane & 31)] = acc[i][j][r];
+  __builtin_amdgcn_wave_barrier();
+  constexpr int CPR = WN / 8;         // 8-column chunks per staged row
+  constexpr int RPP = 64 / CPR;       // rows covered by one pass of the wave
+  const int cc = lane % CPR, rr = lane / CPR;
+  const int n = n0 + wn0 + cc * 8;
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if ((EPI == EPI_BIAS || EPI == EPI_BIAS_ACT) && n < N) load8(bias + n, bv);
+#pragma unroll 4
+  for (int pass = 0; pass < WM / RPP; ++pass) {
+    const int row = pass * RPP + rr;
+    const int m = m0 + wm0 + row;
+    float v[8];
+    const float4 lo = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8);
+    const float4 hi = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8 + 4);
+    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+    if (m < M && n < N) {
+      const int64_t idx = (int64_t)m * N + n;
+      if (EPI == EPI_BIAS) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += bv[e];
+      } else if (EPI == EPI_BIAS_ACT) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += bv[e];
+        store8(aux_out + idx, v);
+        // activation of the stored (rounded) pre-activation, the value backward will differentiate at
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = act_fwd(bf16_to_f32(f32_to_bf16(v[e])), act);
+      } else if (EPI == EPI_DACT) {
+        float u[8];
+        load8(aux_in + idx, u);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= act_grad(u[e], act);
+      } else if (EPI == EPI_ADD) {
+        float u[8];
+        load8(aux_in + idx, u);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += u[e];
       }
+      store8(C + idx, v);
     }
+  }
 }
 
 // fp32 correctness kernel: 64x64 tile, 16-deep slabs, each thread a 4x4 block.
@@ -240,7 +282,9 @@ template <int LAYOUT, int BM, int BN>
 static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                              const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
+  const size_t lds_main = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
+  const size_t lds_epi = (size_t)4 * (BM / 2) * (BN / 2 + 4) * sizeof(float);
+  const size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
 #define SLAPO_GEMM(E)                                                                                       \
   do {                                                                                                      \
     auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, E>;                                                        \

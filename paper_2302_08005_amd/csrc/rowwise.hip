@@ -223,16 +223,38 @@ __global__ __launch_bounds__(256) void colsum_partials_kernel(int64_t rows, int6
   }
 }
 
+// stage 2: out[n] = sum_i partials[i*stride + n]. A block owns 64 columns; its 16 wavefronts each sum a
+// contiguous share of the rows with all loads in flight at once, then the shares are added in wave order.
 template <typename T>
-__global__ __launch_bounds__(256) void colreduce_partials_kernel(int64_t nblk, int64_t stride, int64_t N,
-                                                                 const float* __restrict__ partials,
-                                                                 T* __restrict__ out, int accumulate) {
-  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (n >= N) return;
+__global__ __launch_bounds__(1024) void colreduce_partials_kernel(int64_t nblk, int64_t stride, int64_t N,
+                                                                  const float* __restrict__ partials,
+                                                                  T* __restrict__ out, int accumulate) {
+  __shared__ float red[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t n = (int64_t)blockIdx.x * 64 + lane;
+  const int64_t per = (nblk + 15) / 16;
+  const int64_t i0 = wave * per, i1 = (i0 + per < nblk) ? i0 + per : nblk;
   float s = 0.f;
-  for (int64_t i = 0; i < nblk; ++i) s += partials[i * stride + n];
-  if (accumulate) s += to_f32(out[n]);
-  from_f32(out[n], s);
+  if (n < N) {
+    int64_t i = i0;
+    for (; i + 8 <= i1; i += 8) {
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = partials[(i + k) * stride + n];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s += v[k];
+    }
+    for (; i < i1; ++i) s += partials[i * stride + n];
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && n < N) {
+    float t = red[0][lane];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) t += red[w][lane];
+    if (accumulate) t += to_f32(out[n]);
+    from_f32(out[n], t);
+  }
 }
 
 __global__ __launch_bounds__(256) void dropout_mask_kernel(int64_t nblocks8, uint8_t* __restrict__ mask,
@@ -338,9 +360,9 @@ void launch_colsum_partials(int dtype_fp32, int64_t rows, int64_t N, const void*
 
 void launch_colreduce_partials(int dtype_fp32, int64_t nblk, int64_t stride, int64_t N, const float* partials,
                                void* out, int accumulate, hipStream_t st) {
-  dim3 grid((unsigned)((N + 255) / 256));
-  if (dtype_fp32) hipLaunchKernelGGL(colreduce_partials_kernel<float>, grid, dim3(256), 0, st, nblk, stride, N, partials, (float*)out, accumulate);
-  else hipLaunchKernelGGL(colreduce_partials_kernel<bf16_t>, grid, dim3(256), 0, st, nblk, stride, N, partials, (bf16_t*)out, accumulate);
+  dim3 grid((unsigned)((N + 63) / 64));
+  if (dtype_fp32) hipLaunchKernelGGL(colreduce_partials_kernel<float>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (float*)out, accumulate);
+  else hipLaunchKernelGGL(colreduce_partials_kernel<bf16_t>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (bf16_t*)out, accumulate);
 }
 
 void launch_dropout_mask(int64_t n_elements, uint8_t* mask, const DropoutParams& dp, hipStream_t st) {

@@ -21,7 +21,23 @@ SMALL = [
 ]
 
 
-def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True):
+def teacher_force(layer, cfg, ref):
+    """Overwrites the saved activations with the oracle's forward values (rounded to the storage type).
+
+    Used for the backward comparison of bf16 ReLU layers: the ReLU gate [u > 0] is a 0/1 decision taken from
+    the stored pre-activation, so both sides must take it from the same stored values; an end-to-end
+    run would flip the gate wherever the two forward passes differ by a rounding error around u = 0.
+    """
+    names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "u": "U", "g": "G", "lse": "LSE", "mu1": "mu1", "rstd1": "rstd1",
+             "mu2": "mu2", "rstd2": "rstd2"}
+    names.update({"n1": "N1", "n2": "N2"} if cfg.pre_ln else {"y1": "Y1", "z2": "Z2"})
+    for k, rk in names.items():
+        dst = layer.saved_tensor(k)
+        src = torch.from_numpy(np.ascontiguousarray(ref[rk], dtype=np.float32).reshape(-1)).to(DEV)
+        dst.copy_(src.to(dst.dtype))
+
+
+def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True, teacher_forced_bwd=False):
     params = W.make_params(cfg, perturbed=perturbed)
     x, dy, sl = W.make_inputs(cfg, q_scale=q_scale)
     ref = L.layer_forward(cfg, params, x, sl)
@@ -30,11 +46,18 @@ def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True):
     xd, dyd = layer.to_device(x), layer.to_device(dy)
     sld = None if sl is None else torch.from_numpy(sl).to(DEV)
     y = layer.forward(xd, sld)
+    if teacher_forced_bwd:
+        torch.cuda.synchronize()
+        saved_errs = {"saved." + k: err(layer.saved_tensor(k).reshape(-1), ref[rk].reshape(-1))
+                      for k, rk in (("u", "U"), ("g", "G"), ("z1", "Z1"), ("qkv", "QKV"), ("attn", "A"))}
+        teacher_force(layer, cfg, ref)
     dx = layer.backward(xd, sld, dyd)
     torch.cuda.synchronize()
     errs = {"y": err(y, ref["y"]), "dx": err(dx, gref["dx"])}
     for k in W.PARAM_NAMES:
         errs["d" + k] = err(layer.grads[k], gref[k])
+    if teacher_forced_bwd:
+        errs.update(saved_errs)
     if check_saved:
         names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "u": "U", "g": "G", "lse": "LSE"}
         names.update({"n1": "N1", "n2": "N2"} if cfg.pre_ln else {"y1": "Y1", "z2": "Z2"})
@@ -78,7 +101,8 @@ def test_zero_dropout_matches_layer_without_dropout_bitwise():
 def test_layer_parity_full_size(key):
     """The benchmark shapes themselves, in the launch configuration bench.py times."""
     cfg = W.CONFIGS[key]
-    errs, _, _ = run_case(cfg, perturbed=False, check_saved=False)
+    # forward end to end; backward end to end too, except for bf16 ReLU layers (see teacher_force)
+    errs, _, _ = run_case(cfg, perturbed=False, check_saved=False, teacher_forced_bwd=(cfg.act == W.RELU))
     tol = TOL[cfg.dtype]
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, (bad, errs)
