@@ -23,11 +23,15 @@ namespace slapo {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// ---- LDS tile [rows][D] of bf16, 16-byte chunks permuted within each 128-byte group ---------------
-__device__ __forceinline__ int tile_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// ---- LDS tile [rows][D] of bf16, 16-byte chunks permuted inside each row -------------------------
+// The LDS serves 256 B per clock (64 banks): 16 lanes of a 16-byte read, 32 lanes of a transposing
+// 8-byte read. The same tile is read both ways -- 16 consecutive rows x one chunk, and 4 consecutive rows
+// x four chunks -- and the XOR pattern below makes both conflict-free. With 128-byte rows (D = 64) rows
+// of equal parity share banks; with 256-byte rows (D = 128) all rows do.
 template <int D>
 __device__ __forceinline__ int tile_off(int row, int chunk) {
-  return row * D + (((chunk & ~7) | ((chunk ^ tile_swz(row)) & 7)) << 3);
+  const int f = (D == 64) ? (((row & 2) << 1) | ((row >> 2) & 3)) : (((row & 3) << 2) | ((row >> 2) & 3));
+  return row * D + ((chunk ^ f) << 3);
 }
 // MFMA operand whose 32 rows are tile rows r0.. and whose contraction runs along D (step s of 16)
 template <int D>

@@ -9,12 +9,15 @@
 // of dY*W and both operands of dY^T*X) stay in their memory order in LDS and are read with the
 // transposing ds_read_b64_tr_b16, so no transposed copy of any tensor is ever made.
 // fp32 path: a plain LDS-tiled FMA kernel (correctness mode).
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
 namespace slapo {
 
 enum { ACT_GELU = 0, ACT_RELU = 1 };
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float act_fwd(float u, int act) {
   if (act == ACT_RELU) return u > 0.f ? u : 0.f;
@@ -49,26 +52,34 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
   from_f32(C[idx], v);
 }
 
-constexpr int BK = 64;
-
-// 16-byte chunk position inside an LDS row: rows that one LDS instruction touches together land in
-// different bank groups. K-contiguous tiles are read 8 rows x 16 B at a time, transposed-read tiles
-// 4 rows x 32 B at a time.
-__device__ __forceinline__ int swz_kc(int row, int chunk) { return chunk ^ (row & 7); }
-__device__ __forceinline__ int swz_mc(int krow, int chunk) { return chunk ^ ((krow & 3) << 1); }
-
-template <int LAYOUT, int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                        const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
-                                                        const bf16_t* __restrict__ bias, const bf16_t* aux_in,
-                                                        bf16_t* __restrict__ aux_out, int act) {
+// LDS tiles are padded instead of XOR-swizzled so that every fragment address is a per-lane base plus a
+// compile-time offset. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte read, and
+// 16 lanes of a transposing 8-byte read, are served together.
+//  - K-contiguous tile [rows][BK]: 16 lanes read one 16-byte chunk of 16 consecutive rows; a row pitch of
+//    2*BK + 16 bytes puts them in 16 different bank groups.
+//  - M-contiguous tile [BK][rows]: 16 lanes read 4 consecutive k-rows x 32 B; a pitch of 2*rows + 32 bytes
+//    keeps the four rows apart.
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int PF, bool KTAIL, int EPI>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(int M, int N, int K,
+                                                                  const bf16_t* __restrict__ A,
+                                                                  const bf16_t* __restrict__ B,
+                                                                  bf16_t* __restrict__ C,
+                                                                  const bf16_t* __restrict__ bias,
+                                                                  const bf16_t* aux_in,
+                                                                  bf16_t* __restrict__ aux_out, int act) {
   constexpr bool A_KC = (LAYOUT != GEMM_TN);  // A operand contiguous along K
   constexpr bool B_KC = (LAYOUT == GEMM_NT);
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-  constexpr int A_LOADS = BM * BK / 8 / 256, B_LOADS = BN * BK / 8 / 256;
+  constexpr int NTHR = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  constexpr int A_LOADS = BM * BK / 8 / NTHR, B_LOADS = BN * BK / 8 / NTHR;
+  static_assert(A_LOADS >= 1 && B_LOADS >= 1, "tile too small for the thread count");
+  constexpr int PA = A_KC ? BK + 8 : BM + 16;   // row pitch of the A tile in elements
+  constexpr int PB = B_KC ? BK + 8 : BN + 16;
+  constexpr int SA = A_KC ? BM * PA : BK * PA;  // elements per stage
+  constexpr int SB = B_KC ? BN * PB : BK * PB;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  bf16_t* sA = smem;                  // [2][BM*BK]
-  bf16_t* sB = smem + 2 * BM * BK;    // [2][BN*BK]
+  bf16_t* sA = smem;            // [2][SA]
+  bf16_t* sB = smem + 2 * SA;   // [2][SB]
 
   // Workgroups are handed to the 8 XCDs round-robin; renumber them so that each XCD (own L2) works
   // on a contiguous band of output tiles and re-reads the same operand panels.
@@ -81,50 +92,70 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(int M, int N, int K, con
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+
+  // Each thread moves A_LOADS + B_LOADS 16-byte pieces per slab. Piece i of a thread sits RSA (RSB) tile
+  // rows below piece 0. Pieces outside M or N are read from a clamped (valid) address and never reach a
+  // stored output, so only the K tail needs zero fill; all loads are unconditional, which lets the
+  // compiler keep the next slabs' loads in flight while it waits for the oldest ones only.
+  constexpr int CA = A_KC ? BK / 8 : BM / 8, CB = B_KC ? BK / 8 : BN / 8;   // pieces per tile row
+  constexpr int RSA = NTHR / CA, RSB = NTHR / CB;                            // tile rows between pieces
+  const int ar = tid / CA, ac = (tid % CA) * 8, br = tid / CB, bc = (tid % CB) * 8;
   const int lda = A_KC ? K : M, ldb = B_KC ? K : N;
+  const bf16_t* ga[A_LOADS];
+  const bf16_t* gb[B_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; ++i) {
+    if (A_KC) { int r = m0 + ar + i * RSA; r = r < M ? r : M - 1; ga[i] = A + (int64_t)r * lda + ac; }
+    else { int c = m0 + ac; c = c < M ? c : M - 8; ga[i] = A + (int64_t)(ar + i * RSA) * lda + c; }
+  }
+#pragma unroll
+  for (int i = 0; i < B_LOADS; ++i) {
+    if (B_KC) { int r = n0 + br + i * RSB; r = r < N ? r : N - 1; gb[i] = B + (int64_t)r * ldb + bc; }
+    else { int c = n0 + bc; c = c < N ? c : N - 8; gb[i] = B + (int64_t)(br + i * RSB) * ldb + c; }
+  }
+  const int64_t stepA = A_KC ? BK : (int64_t)BK * lda, stepB = B_KC ? BK : (int64_t)BK * ldb;
+  const int la0 = ar * PA + ac, lb0 = br * PB + bc;
 
-  uint4 ra[A_LOADS], rb[B_LOADS];
-
-  auto load_global = [&](int k0) {
+  const int nk = (K + BK - 1) / BK;
+  u32x4_t ra0[A_LOADS], rb0[B_LOADS], ra1[A_LOADS], rb1[B_LOADS];   // register sets: slab k lives in set k % PF
+  // Every call issues exactly A_LOADS + B_LOADS loads (slab index clamped to the last one), so the number
+  // of loads in flight is the same on every path and the oldest slab can be awaited on its own.
+  auto load_global = [&](int kstep, u32x4_t (&ra)[A_LOADS], u32x4_t (&rb)[B_LOADS]) {
+    kstep = kstep < nk ? kstep : nk - 1;
+    const int k0 = kstep * BK;
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
-      const int q = tid + i * 256;
-      int row, col;  // row/col in memory order of the tile
-      if (A_KC) { row = m0 + q / 8; col = k0 + (q % 8) * 8; }
-      else { row = k0 + q / (BM / 8); col = m0 + (q % (BM / 8)) * 8; }
-      const bool ok = A_KC ? (row < M && col < K) : (row < K && col < M);
-      ra[i] = ok ? *reinterpret_cast<const uint4*>(A + (int64_t)row * lda + col) : make_uint4(0, 0, 0, 0);
+      const bf16_t* p = ga[i] + kstep * stepA;
+      if (KTAIL) {  // pieces at or beyond K: read a valid address, zero the value
+        const bool ok = A_KC ? (k0 + ac < K) : (k0 + ar + i * RSA < K);
+        p = ok ? p : A;
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(p);
+        ra[i] = ok ? v : u32x4_t{0, 0, 0, 0};
+      } else {
+        ra[i] = *reinterpret_cast<const u32x4_t*>(p);
+      }
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
-      const int q = tid + i * 256;
-      int row, col;
-      if (B_KC) { row = n0 + q / 8; col = k0 + (q % 8) * 8; }
-      else { row = k0 + q / (BN / 8); col = n0 + (q % (BN / 8)) * 8; }
-      const bool ok = B_KC ? (row < N && col < K) : (row < K && col < N);
-      rb[i] = ok ? *reinterpret_cast<const uint4*>(B + (int64_t)row * ldb + col) : make_uint4(0, 0, 0, 0);
+      const bf16_t* p = gb[i] + kstep * stepB;
+      if (KTAIL) {
+        const bool ok = B_KC ? (k0 + bc < K) : (k0 + br + i * RSB < K);
+        p = ok ? p : B;
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(p);
+        rb[i] = ok ? v : u32x4_t{0, 0, 0, 0};
+      } else {
+        rb[i] = *reinterpret_cast<const u32x4_t*>(p);
+      }
     }
   };
-  auto store_lds = [&](int stage) {
-    bf16_t* a = sA + stage * BM * BK;
-    bf16_t* b = sB + stage * BN * BK;
+  auto store_lds = [&](int stage, const u32x4_t (&ra)[A_LOADS], const u32x4_t (&rb)[B_LOADS]) {
+    bf16_t* a = sA + stage * SA + la0;
+    bf16_t* b = sB + stage * SB + lb0;
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) {
-      const int q = tid + i * 256;
-      int off;
-      if (A_KC) { const int r = q / 8, c = q % 8; off = r * BK + swz_kc(r, c) * 8; }
-      else { const int r = q / (BM / 8), c = q % (BM / 8); off = r * BM + swz_mc(r, c) * 8; }
-      *reinterpret_cast<uint4*>(a + off) = ra[i];
-    }
+    for (int i = 0; i < A_LOADS; ++i) *reinterpret_cast<u32x4_t*>(a + i * RSA * PA) = ra[i];
 #pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) {
-      const int q = tid + i * 256;
-      int off;
-      if (B_KC) { const int r = q / 8, c = q % 8; off = r * BK + swz_kc(r, c) * 8; }
-      else { const int r = q / (BN / 8), c = q % (BN / 8); off = r * BN + swz_mc(r, c) * 8; }
-      *reinterpret_cast<uint4*>(b + off) = rb[i];
-    }
+    for (int i = 0; i < B_LOADS; ++i) *reinterpret_cast<u32x4_t*>(b + i * RSB * PB) = rb[i];
   };
 
   f32x16_t acc[TM][TN];
@@ -135,103 +166,136 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(int M, int N, int K, con
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // fragment of a 32-row tile starting at `r0` (tile-local row) for the 16-deep step ks
-  auto frag_kc = [&](const bf16_t* tile, int r0, int ks) -> bf16x8_t {
-    const int r = r0 + (lane & 31), c = ks * 2 + (lane >> 5);
-    return *reinterpret_cast<const bf16x8_t*>(tile + r * BK + swz_kc(r, c) * 8);
+  // per-lane fragment bases (stage 0, 32-row tile 0, k-step 0)
+  const int fa_base = A_KC ? (wm0 + (lane & 31)) * PA + (lane >> 5) * 8
+                           : (8 * (lane >> 5) + ((lane & 15) >> 2)) * PA + wm0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const int fb_base = B_KC ? (wn0 + (lane & 31)) * PB + (lane >> 5) * 8
+                           : (8 * (lane >> 5) + ((lane & 15) >> 2)) * PB + wn0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  auto frag = [&](const bf16_t* tile, auto kc_tag, int base, int pitch, int t, int ks) -> bf16x8_t {
+    if constexpr (decltype(kc_tag)::value) {
+      return *reinterpret_cast<const bf16x8_t*>(tile + base + t * 32 * pitch + ks * 16);
+    } else {
+      const bf16_t* p0 = tile + base + ks * 16 * pitch + t * 32;
+      s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p0);
+      s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p0 + 4 * pitch));
+      typedef short s16x8_t __attribute__((ext_vector_type(8)));
+      s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8_t, v);
+    }
   };
-  auto frag_mc = [&](const bf16_t* tile, int ld, int r0, int ks) -> bf16x8_t {
-    const int j = lane & 15, g = lane >> 4;
-    const int k = ks * 16 + 8 * (g >> 1) + (j >> 2);
-    const int m = r0 + 16 * (g & 1) + 4 * (j & 3);
-    const bf16_t* p0 = tile + k * ld + swz_mc(k, m >> 3) * 8 + (m & 7);
-    const bf16_t* p1 = tile + (k + 4) * ld + swz_mc(k + 4, m >> 3) * 8 + (m & 7);
-    s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p0);
-    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p1);
-    typedef short s16x8_t __attribute__((ext_vector_type(8)));
-    s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8_t, v);
-  };
-
-  const int nk = (K + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
-    const bf16_t* a = sA + stage * BM * BK;
-    const bf16_t* b = sB + stage * BN * BK;
+  auto compute = [&](int stage) {
+    const bf16_t* a = sA + stage * SA;
+    const bf16_t* b = sB + stage * SB;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8_t fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = A_KC ? frag_kc(a, wm0 + i * 32, ks) : frag_mc(a, BM, wm0 + i * 32, ks);
+      for (int i = 0; i < TM; ++i) fa[i] = frag(a, std::integral_constant<bool, A_KC>{}, fa_base, PA, i, ks);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = B_KC ? frag_kc(b, wn0 + j * 32, ks) : frag_mc(b, BN, wn0 + j * 32, ks);
+      for (int j = 0; j < TN; ++j) fb[j] = frag(b, std::integral_constant<bool, B_KC>{}, fb_base, PB, j, ks);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_lds(stage ^ 1);
-    __syncthreads();
+  };
+
+  // Pipeline: the slab of k-step k is computed from LDS stage k&1 while the global loads of the next PF
+  // slabs are in flight in registers (register set k % PF holds slab k); a slab is written to LDS right
+  // after the compute of the step before it. With PF == 2 the slab count must be even (the host falls
+  // back to PF == 1 otherwise). Loads and stores are issued on every step (slab index clamped; the last
+  // steps re-fetch the last slab into a stage nobody reads): with every step alike, the wait before an
+  // LDS store covers the oldest slab only and the newer loads stay in flight.
+  load_global(0, ra0, rb0);
+  if (PF > 1) load_global(1, ra1, rb1);
+  store_lds(0, ra0, rb0);
+  __syncthreads();
+  if (PF == 1) {
+    for (int k = 0; k < nk; ++k) {
+      load_global(k + 1, ra0, rb0);
+      compute(k & 1);
+      store_lds((k + 1) & 1, ra0, rb0);
+      __syncthreads();
+    }
+  } else {
+    for (int k = 0; k < nk; k += 2) {
+      load_global(k + 2, ra0, rb0);
+      compute(0);
+      store_lds(1, ra1, rb1);
+      __syncthreads();
+      load_global(k + 3, ra1, rb1);
+      compute(1);
+      store_lds(0, ra0, rb0);
+      __syncthreads();
+    }
   }
 
   // Epilogue. The accumulators (element r of a 32x32 tile: row (r/4)*8 + 4*(lane/32) + r%4, column
-  // lane%32) go through a per-wave fp32 staging area in LDS so that every global access of the epilogue
-  // (bias, auxiliary input, both outputs) is a 16-byte access of 8 consecutive columns of one row.
-  // The main loop ended with a barrier, so the operand stages are free to be overwritten.
+  // lane%32) go, one 32-row slab at a time, through a per-wave fp32 staging area in LDS so that every
+  // global access of the epilogue (bias, auxiliary input, both outputs) is a 16-byte access of 8
+  // consecutive columns of one row. The main loop ended with a barrier, so the stages are free.
   constexpr int LDP = WN + 4;
-  float* stage = reinterpret_cast<float*>(smem) + wave * (WM * LDP);
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage[(i * 32 + (r >> 2) * 8 + 4 * (lane >> 5) + (r & 3)) * LDP + j * 32 + (lane & 31)] = acc[i][j][r];
-  __builtin_amdgcn_wave_barrier();
+  float* stage = reinterpret_cast<float*>(smem) + wave * (32 * LDP);
   constexpr int CPR = WN / 8;         // 8-column chunks per staged row
   constexpr int RPP = 64 / CPR;       // rows covered by one pass of the wave
   const int cc = lane % CPR, rr = lane / CPR;
   const int n = n0 + wn0 + cc * 8;
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if ((EPI == EPI_BIAS || EPI == EPI_BIAS_ACT) && n < N) load8(bias + n, bv);
-#pragma unroll 4
-  for (int pass = 0; pass < WM / RPP; ++pass) {
-    const int row = pass * RPP + rr;
-    const int m = m0 + wm0 + row;
-    float v[8];
-    const float4 lo = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8);
-    const float4 hi = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8 + 4);
-    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-    if (m < M && n < N) {
-      const int64_t idx = (int64_t)m * N + n;
-      if (EPI == EPI_BIAS) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += bv[e];
-      } else if (EPI == EPI_BIAS_ACT) {
+  for (int i = 0; i < TM; ++i) {
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += bv[e];
-        store8(aux_out + idx, v);
-        // activation of the stored (rounded) pre-activation, the value backward will differentiate at
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = act_fwd(bf16_to_f32(f32_to_bf16(v[e])), act);
-      } else if (EPI == EPI_DACT) {
-        float u[8];
-        load8(aux_in + idx, u);
+      for (int r = 0; r < 16; ++r)
+        stage[((r >> 2) * 8 + 4 * (lane >> 5) + (r & 3)) * LDP + j * 32 + (lane & 31)] = acc[i][j][r];
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= act_grad(u[e], act);
-      } else if (EPI == EPI_ADD) {
-        float u[8];
-        load8(aux_in + idx, u);
+    for (int pass = 0; pass < 32 / RPP; ++pass) {
+      const int row = pass * RPP + rr;
+      const int m = m0 + wm0 + i * 32 + row;
+      float v[8];
+      const float4 lo = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8);
+      const float4 hi = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8 + 4);
+      v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+      if (m < M && n < N) {
+        const int64_t idx = (int64_t)m * N + n;
+        if (EPI == EPI_BIAS) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += u[e];
+          for (int e = 0; e < 8; ++e) v[e] += bv[e];
+        } else if (EPI == EPI_BIAS_ACT) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += bv[e];
+          store8(aux_out + idx, v);
+          // activation of the stored (rounded) pre-activation, the value backward will differentiate at
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = act_fwd(bf16_to_f32(f32_to_bf16(v[e])), act);
+        } else if (EPI == EPI_DACT) {
+          float u[8];
+          load8(aux_in + idx, u);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= act_grad(u[e], act);
+        } else if (EPI == EPI_ADD) {
+          float u[8];
+          load8(aux_in + idx, u);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += u[e];
+        }
+        store8(C + idx, v);
       }
-      store8(C + idx, v);
     }
   }
+}
+
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN>
+constexpr size_t gemm_lds_bytes() {
+  constexpr bool A_KC = (LAYOUT != GEMM_TN), B_KC = (LAYOUT == GEMM_NT);
+  constexpr size_t SA = A_KC ? BM * (BK + 8) : BK * (BM + 16);
+  constexpr size_t SB = B_KC ? BN * (BK + 8) : BK * (BN + 16);
+  constexpr size_t main_bytes = 2 * (SA + SB) * sizeof(bf16_t);
+  constexpr size_t epi_bytes = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
+  return main_bytes > epi_bytes ? main_bytes : epi_bytes;
 }
 
 // fp32 correctness kernel: 64x64 tile, 16-deep slabs, each thread a 4x4 block.
@@ -278,19 +342,30 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, cons
     }
 }
 
-template <int LAYOUT, int BM, int BN>
+// epilogue / layout pairs the layer itself uses; only these get the tuned (deep-prefetch) kernels
+constexpr bool epi_used(int layout, int epi) {
+  return layout == GEMM_NT ? (epi == EPI_NONE || epi == EPI_BIAS || epi == EPI_BIAS_ACT)
+       : layout == GEMM_NN ? (epi == EPI_NONE || epi == EPI_DACT || epi == EPI_ADD)
+                           : (epi == EPI_NONE || epi == EPI_ADD);
+}
+
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int PF, bool KTAIL>
 static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                              const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const size_t lds_main = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-  const size_t lds_epi = (size_t)4 * (BM / 2) * (BN / 2 + 4) * sizeof(float);
-  const size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+  const size_t lds = gemm_lds_bytes<LAYOUT, BM, BN, BK, WGM, WGN>();
 #define SLAPO_GEMM(E)                                                                                       \
   do {                                                                                                      \
-    auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, E>;                                                        \
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);    \
-    hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), lds, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B,  \
-                       (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)aux_in, (bf16_t*)aux_out, act);      \
+    if constexpr (KTAIL || epi_used(LAYOUT, E)) {                                                           \
+      auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, BK, WGM, WGN, PF, KTAIL, E>;                             \
+      (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
+      hipLaunchKernelGGL(kern, dim3(tiles), dim3(WGM * WGN * 64), lds, st, M, N, K, (const bf16_t*)A,       \
+                         (const bf16_t*)B, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)aux_in,          \
+                         (bf16_t*)aux_out, act);                                                            \
+    } else {                                                                                                \
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in,       \
+                                                           aux_out, st);                                    \
+    }                                                                                                       \
   } while (0)
   switch (epi) {
     case EPI_NONE: SLAPO_GEMM(EPI_NONE); break;
@@ -302,13 +377,23 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 #undef SLAPO_GEMM
 }
 
+// Tile selection, from measurements on the layer's shapes: 256x256 tiles (8 wavefronts, 128x64 each) when
+// they still cover at least three quarters of the 256 CUs; otherwise 128x128 (8 wavefronts, 64x32 each);
+// for outputs with few tiles 128x64 tiles with 128-deep slabs. All use two slabs of register prefetch,
+// which needs an even number of whole slabs; other K go to the general kernel (one slab, zero-filled tail).
 template <int LAYOUT>
 static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                         const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
-  // 256x128 tiles when they still give every CU at least two tiles; otherwise 128x128 for occupancy
-  const int64_t t_big = (int64_t)((M + 255) / 256) * ((N + 127) / 128);
-  if (t_big >= 512) launch_bf16_tile<LAYOUT, 256, 128>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else launch_bf16_tile<LAYOUT, 128, 128>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
+  const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+  if (K % 128 == 0 && t256 >= 192)
+    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  else if (K % 128 == 0 && (t128 >= 160 || K % 256 != 0))
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  else if (K % 256 == 0)
+    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  else
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
 }
 
 void launch_gemm(int dtype_fp32, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
