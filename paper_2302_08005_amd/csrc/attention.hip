@@ -23,33 +23,37 @@ namespace slapo {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// ---- LDS tile [rows][D] of bf16, 16-byte chunks permuted inside each row -------------------------
-// The LDS serves 256 B per clock (64 banks): 16 lanes of a 16-byte read, 32 lanes of a transposing
-// 8-byte read. The same tile is read both ways -- 16 consecutive rows x one chunk, and 4 consecutive rows
-// x four chunks -- and the XOR pattern below makes both conflict-free. With 128-byte rows (D = 64) rows
-// of equal parity share banks; with 256-byte rows (D = 128) all rows do.
+// ---- LDS tile [rows][D] of bf16 with rows padded by 16 bytes --------------------------------------
+// The LDS serves 256 B per clock (64 banks of 4 B), 16 lanes at a time. The same tile is read two ways:
+// 16 consecutive rows x one 16-byte chunk (operand with the contraction along D), and 4 consecutive rows
+// x 32 B with the transposing 8-byte read (operand with the contraction along the rows). A row pitch of
+// 2*D + 16 bytes keeps both conflict-free, and every fragment address is a per-lane base plus a
+// compile-time offset, so the inner loops spend no vector instructions on addressing.
 template <int D>
-__device__ __forceinline__ int tile_off(int row, int chunk) {
-  const int f = (D == 64) ? (((row & 2) << 1) | ((row >> 2) & 3)) : (((row & 3) << 2) | ((row >> 2) & 3));
-  return row * D + ((chunk ^ f) << 3);
+struct Tile {
+  static constexpr int P = D + 8;          // row pitch in elements
+  static constexpr int ELEMS = 64 * P;     // one 64-row tile
+};
+// per-lane bases, computed once per kernel
+template <int D>
+__device__ __forceinline__ int rows_base(int lane) { return (lane & 31) * Tile<D>::P + (lane >> 5) * 8; }
+template <int D>
+__device__ __forceinline__ int tr_base(int lane) {
+  const int j = lane & 15, g = lane >> 4;
+  return (4 * (g >> 1) + (j >> 2)) * Tile<D>::P + 16 * (g & 1) + 4 * (j & 3);
 }
 // MFMA operand whose 32 rows are tile rows r0.. and whose contraction runs along D (step s of 16)
 template <int D>
-__device__ __forceinline__ bf16x8_t frag_rows(const bf16_t* tile, int r0, int s, int lane) {
-  const int r = r0 + (lane & 31);
-  return *reinterpret_cast<const bf16x8_t*>(tile + tile_off<D>(r, 2 * s + (lane >> 5)));
+__device__ __forceinline__ bf16x8_t frag_rows(const bf16_t* tile, int base, int r0, int s) {
+  return *reinterpret_cast<const bf16x8_t*>(tile + base + r0 * Tile<D>::P + 16 * s);
 }
 // MFMA operand whose 32 rows are tile COLUMNS t*32.. and whose contraction runs over tile rows
 // c0 + {4kc..4kc+3, 8+4kc..8+4kc+3} (kc = lane/32): the order in which a 32x32 accumulator holds them.
 template <int D>
-__device__ __forceinline__ bf16x8_t frag_tr(const bf16_t* tile, int c0, int t, int lane) {
-  const int j = lane & 15, g = lane >> 4;
-  const int row = c0 + 4 * (g >> 1) + (j >> 2);
-  const int col = t * 32 + 16 * (g & 1) + 4 * (j & 3);
-  const bf16_t* p0 = tile + tile_off<D>(row, col >> 3) + (col & 7);
-  const bf16_t* p1 = tile + tile_off<D>(row + 8, col >> 3) + (col & 7);
+__device__ __forceinline__ bf16x8_t frag_tr(const bf16_t* tile, int base, int c0, int t) {
+  const bf16_t* p0 = tile + base + c0 * Tile<D>::P + t * 32;
   s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p0);
-  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p1);
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p0 + 8 * Tile<D>::P));
   typedef short s16x8_t __attribute__((ext_vector_type(8)));
   s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8_t, v);
@@ -64,28 +68,28 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& v, int h) {
 // row index inside a 32x32 accumulator tile of register r
 __device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + 4 * (lane >> 5) + (r & 3); }
 
-// 64 x D tile: global rows (clamped to `last_row`) -> registers -> LDS
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// 64 x D tile: global rows (clamped to `last_row`, so every load is unconditional) -> registers -> LDS.
+// Rows past the end of the sequence are never zeroed: the kernels mask the scores that involve them.
 template <int D>
-struct TileMover {
+struct TileRegs {
   static constexpr int N = 64 * D / 8 / 256;
-  uint4 r[N];
-  __device__ __forceinline__ void load(const bf16_t* src, int64_t row_stride, int row0, int last_row, int tid,
-                                       int zero_from) {
+  u32x4_t r[N];
+  __device__ __forceinline__ void load(const bf16_t* src, int64_t row_stride, int row0, int last_row, int tid) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int q = tid + i * 256, row = q / (D / 8), c = q % (D / 8);
       int gr = row0 + row;
-      const bool zero = gr >= zero_from;
       gr = gr > last_row ? last_row : gr;
-      r[i] = *reinterpret_cast<const uint4*>(src + (int64_t)gr * row_stride + c * 8);
-      if (zero) r[i] = make_uint4(0, 0, 0, 0);
+      r[i] = *reinterpret_cast<const u32x4_t*>(src + (int64_t)gr * row_stride + c * 8);
     }
   }
   __device__ __forceinline__ void store(bf16_t* tile, int tid) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int q = tid + i * 256, row = q / (D / 8), c = q % (D / 8);
-      *reinterpret_cast<uint4*>(tile + tile_off<D>(row, c)) = r[i];
+      *reinterpret_cast<u32x4_t*>(tile + row * Tile<D>::P + c * 8) = r[i];
     }
   }
 };
@@ -96,16 +100,44 @@ __device__ __forceinline__ int visible_keys(const AttnShape& sh, const int32_t* 
   return n;
 }
 
+// Tile pipeline shared by the three kernels: tile t is computed from LDS stage t&1 while the loads of
+// tiles t+1 and t+2 are in flight in two register sets. Loads and stores are issued on every step with a
+// clamped tile index (the surplus ones land in a stage nobody reads), so the number of loads in flight is
+// the same on every path and the wait before an LDS store covers the oldest tile only.
+#define SLAPO_TILE_PIPELINE(n_tiles, LOAD, STORE, COMPUTE)        \
+  do {                                                            \
+    if ((n_tiles) > 0) {                                          \
+      const int last_ = (n_tiles)-1;                              \
+      LOAD(0, 0);                                                 \
+      LOAD(1, (1 < last_ ? 1 : last_));                           \
+      STORE(0, 0);                                                \
+      __syncthreads();                                            \
+      for (int it_ = 0; it_ < (n_tiles); it_ += 2) {              \
+        LOAD(0, (it_ + 2 < last_ ? it_ + 2 : last_));             \
+        COMPUTE(0, it_);                                          \
+        STORE(1, 1);                                              \
+        __syncthreads();                                          \
+        if (it_ + 1 >= (n_tiles)) break;                          \
+        LOAD(1, (it_ + 3 < last_ ? it_ + 3 : last_));             \
+        COMPUTE(1, it_ + 1);                                      \
+        STORE(0, 0);                                              \
+        __syncthreads();                                          \
+      }                                                           \
+    }                                                             \
+  } while (0)
+
 // =================================== forward =====================================================
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                             const int32_t* __restrict__ seqlens,
                                                             bf16_t* __restrict__ out, float* __restrict__ lse) {
   constexpr int NS = D / 16, NT = D / 32;
+  constexpr int TE = Tile<D>::ELEMS;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int S = sh.seq, H = sh.hidden;
   const int b = blockIdx.z, a = blockIdx.y, q_base = blockIdx.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
+  const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
   const int64_t rs = 3 * (int64_t)H;
   const bf16_t* base = qkv + (int64_t)b * S * rs + a * D;
   const int kv_len = visible_keys(sh, seqlens, b);
@@ -114,8 +146,8 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
   const int n_tiles = (kv_end + 63) / 64;
   const int my_q = q_base + 32 * wave + (lane & 31);
   const int q_ld = my_q < S ? my_q : S - 1;
-  const int wave_q_max = q_base + 32 * wave + 31;
-  const float sl2 = LOG2E * rsqrtf((float)D);
+  const int wave_q_min = q_base + 32 * wave, wave_q_max = wave_q_min + 31;
+  const float scale = rsqrtf((float)D), sl2 = LOG2E * scale;
 
   bf16x8_t qf[NS];
 #pragma unroll
@@ -126,83 +158,74 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
   for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
-  float m = -INFINITY, l = 0.f;
+  float m = -INFINITY, l = 0.f;   // running maximum (raw score units) and sum of this lane's half row
 
-  TileMover<D> mk, mv;
-  if (n_tiles > 0) {
-    mk.load(base + H, rs, 0, S - 1, tid, S);
-    mv.load(base + 2 * H, rs, 0, S - 1, tid, S);
-    mk.store(smem, tid);
-    mv.store(smem + 64 * D, tid);
-  }
-  __syncthreads();
-  for (int it = 0; it < n_tiles; ++it) {
+  TileRegs<D> rk[2], rv[2];
+#define FWD_LOAD(set, t) do { rk[set].load(base + H, rs, (t) * 64, S - 1, tid); rv[set].load(base + 2 * H, rs, (t) * 64, S - 1, tid); } while (0)
+#define FWD_STORE(stage, set) do { rk[set].store(smem + (stage) * 2 * TE, tid); rv[set].store(smem + (stage) * 2 * TE + TE, tid); } while (0)
+  auto compute = [&](int stage, int it) {
     const int kv0 = it * 64;
-    const bf16_t* kt = smem + (it & 1) * 128 * D;
-    const bf16_t* vt = kt + 64 * D;
-    if (it + 1 < n_tiles) {
-      mk.load(base + H, rs, kv0 + 64, S - 1, tid, S);
-      mv.load(base + 2 * H, rs, kv0 + 64, S - 1, tid, S);
+    if (sh.causal && kv0 > wave_q_max) return;   // every key of the tile lies in this wave's future
+    const bf16_t* kt = smem + stage * 2 * TE;
+    const bf16_t* vt = kt + TE;
+    f32x16_t sc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sc[i][r] = 0.f;
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        sc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(kt, fr_base, i * 32, s), qf[s], sc[i], 0, 0, 0);
     }
-    if (!sh.causal || kv0 <= wave_q_max) {
-      f32x16_t sc[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sc[i][r] = 0.f;
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-          sc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(kt, i * 32, s, lane), qf[s], sc[i], 0, 0, 0);
-      }
-      const bool edge = (kv0 + 64 > kv_len) || (sh.causal && kv0 + 63 > q_base + 32 * wave);
-      float mx = -INFINITY;
+    if ((kv0 + 64 > kv_len) || (sh.causal && kv0 + 63 > wave_q_min)) {   // tile crosses a mask boundary
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float v = sc[i][r] * sl2;
-          if (edge) {
-            const int kv = kv0 + i * 32 + acc_row(r, lane);
-            if (kv >= kv_len || (sh.causal && kv > my_q)) v = -INFINITY;
-          }
-          sc[i][r] = v;
-          mx = fmaxf(mx, v);
+          const int kv = kv0 + i * 32 + acc_row(r, lane);
+          if (kv >= kv_len || (sh.causal && kv > my_q)) sc[i][r] = -INFINITY;
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
-      l *= alpha;
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[i][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    if (__any(m_new > m)) {   // some row's maximum grew: rescale what has been accumulated
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * sl2);   // m = -inf gives 0; m = m_new gives 1
+      const float al = (m_new == -INFINITY) ? 0.f : alpha;             // avoids inf - inf for rows still empty
+      l *= al;
 #pragma unroll
       for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(sc[i][r] - m_safe);
-          sc[i][r] = p;
-          l += p;
-        }
+        for (int r = 0; r < 16; ++r) o[t][r] *= al;
       m = m_new;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const bf16x8_t pf = pack8(sc[i], h);
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(vt, i * 32 + 16 * h, t, lane), pf, o[t], 0, 0, 0);
-        }
     }
-    if (it + 1 < n_tiles) {
-      bf16_t* nk = smem + ((it + 1) & 1) * 128 * D;
-      mk.store(nk, tid);
-      mv.store(nk + 64 * D, tid);
-    }
-    __syncthreads();
-  }
+    const float mb = (m == -INFINITY) ? 0.f : m * sl2;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sc[i][r], sl2, -mb));
+        sc[i][r] = p;
+        l += p;
+      }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const bf16x8_t pf = pack8(sc[i], h);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(vt, ft_base, i * 32 + 16 * h, t), pf, o[t], 0, 0, 0);
+      }
+  };
+  SLAPO_TILE_PIPELINE(n_tiles, FWD_LOAD, FWD_STORE, compute);
+#undef FWD_LOAD
+#undef FWD_STORE
+
   const float l_tot = l + __shfl_xor(l, 32, 64);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (my_q < S) {
@@ -216,7 +239,7 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
         w.y = pack_bf16x2(o[t][4 * g + 2] * inv, o[t][4 * g + 3] * inv);
         *reinterpret_cast<uint2*>(orow + t * 32 + g * 8 + 4 * kc) = w;
       }
-    if (kc == 0) lse[((int64_t)b * sh.heads + a) * S + my_q] = l_tot > 0.f ? (m + __log2f(l_tot)) * LN2 : -INFINITY;
+    if (kc == 0) lse[((int64_t)b * sh.heads + a) * S + my_q] = l_tot > 0.f ? m * scale + __logf(l_tot) : -INFINITY;
   }
 }
 
@@ -263,11 +286,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
                                                                  const float* __restrict__ delta,
                                                                  bf16_t* __restrict__ dqkv) {
   constexpr int NS = D / 16, NT = D / 32;
-  constexpr int STAGE = 128 * D + 256;  // bf16 units: Q tile, dO tile, 64 lse + 64 delta floats
+  constexpr int TE = Tile<D>::ELEMS;
+  constexpr int STAGE = 2 * TE + 256;   // bf16 units: Q tile, dO tile, 64 lse + 64 delta floats
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int S = sh.seq, H = sh.hidden;
   const int b = blockIdx.z, a = blockIdx.y, kv_base = blockIdx.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
+  const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
   const int64_t rs = 3 * (int64_t)H;
   const bf16_t* base = qkv + (int64_t)b * S * rs + a * D;
   const bf16_t* dobase = dout + (int64_t)b * S * H + a * D;
@@ -277,6 +302,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
   const int my_kv = kv_base + 32 * wave + (lane & 31);
   const int kv_ld = my_kv < S ? my_kv : S - 1;
   const int wave_kv_min = kv_base + 32 * wave;
+  const bool wave_kv_edge = wave_kv_min + 32 > kv_len;   // some of this wave's keys are hidden
   const float scale = rsqrtf((float)D), sl2 = LOG2E * scale;
 
   bf16x8_t kf[NS], vf[NS];
@@ -292,66 +318,68 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
     for (int r = 0; r < 16; ++r) dk[t][r] = dv[t][r] = 0.f;
 
   const int q_first = sh.causal ? (kv_base / 64) : 0;
-  const int q_tiles = (kv_base < kv_len) ? (S + 63) / 64 : q_first;  // nothing to do for fully hidden keys
-  TileMover<D> mq, md;
-  float aux = 0.f;
-  auto load_tile = [&](int qt) {
-    const int q0 = qt * 64;
-    mq.load(base, rs, q0, S - 1, tid, S);
-    md.load(dobase, H, q0, S - 1, tid, S);
-    if (tid < 128) {
-      const int q = q0 + (tid & 63);
-      aux = 0.f;
-      if (q < S) aux = tid < 64 ? lse_row[q] * LOG2E : delta_row[q];
-    }
+  const int n_tiles = (kv_base < kv_len) ? (S + 63) / 64 - q_first : 0;  // nothing to do for fully hidden keys
+  TileRegs<D> rq[2], rd[2];
+  float aux[2] = {0.f, 0.f};
+  const int stat_row = tid & 63;
+  auto load_stats = [&](int q0) -> float {
+    int q = q0 + stat_row;
+    q = q < S ? q : S - 1;
+    // threads 0..63 carry lse (in log2 units), threads 64..127 delta; the others re-read delta and drop it
+    return tid < 64 ? lse_row[q] * LOG2E : delta_row[q];
   };
-  auto store_tile = [&](int stage) {
-    bf16_t* t0 = smem + stage * STAGE;
-    mq.store(t0, tid);
-    md.store(t0 + 64 * D, tid);
-    if (tid < 128) reinterpret_cast<float*>(t0 + 128 * D)[tid] = aux;
-  };
-  if (q_first < q_tiles) { load_tile(q_first); store_tile(0); }
-  __syncthreads();
-  for (int qt = q_first; qt < q_tiles; ++qt) {
-    const int stage = (qt - q_first) & 1, q0 = qt * 64;
+#define DKV_LOAD(set, t) do { const int q0_ = (q_first + (t)) * 64; rq[set].load(base, rs, q0_, S - 1, tid); rd[set].load(dobase, H, q0_, S - 1, tid); aux[set] = load_stats(q0_); } while (0)
+#define DKV_STORE(stage, set) do { bf16_t* t0_ = smem + (stage) * STAGE; rq[set].store(t0_, tid); rd[set].store(t0_ + TE, tid); if (tid < 128) reinterpret_cast<float*>(t0_ + 2 * TE)[tid] = aux[set]; } while (0)
+  auto compute = [&](int stage, int it) {
+    const int q0 = (q_first + it) * 64;
     const bf16_t* qtile = smem + stage * STAGE;
-    const bf16_t* dtile = qtile + 64 * D;
-    const float* stats = reinterpret_cast<const float*>(qtile + 128 * D);
-    if (qt + 1 < q_tiles) load_tile(qt + 1);
+    const bf16_t* dtile = qtile + TE;
+    const float* stats = reinterpret_cast<const float*>(qtile + 2 * TE);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      if (sh.causal && q0 + i * 32 + 31 < wave_kv_min) continue;  // every query of this sub-tile precedes my keys
+      const int qs = q0 + i * 32;
+      if (sh.causal && qs + 31 < wave_kv_min) continue;  // every query of this sub-tile precedes my keys
       f32x16_t sc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(qtile, i * 32, s, lane), kf[s], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(dtile, i * 32, s, lane), vf[s], dp, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(qtile, fr_base, i * 32, s), kf[s], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(dtile, fr_base, i * 32, s), vf[s], dp, 0, 0, 0);
       }
+      const bool edge = wave_kv_edge || (qs + 32 > S) || (sh.causal && qs < wave_kv_min + 32);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int qi = i * 32 + acc_row(r, lane);
-        const int q = q0 + qi;
-        float p = __builtin_amdgcn_exp2f(sc[r] * sl2 - stats[qi]);
-        if (my_kv >= kv_len || q >= S || (sh.causal && my_kv > q)) p = 0.f;
-        sc[r] = p;
-        dp[r] = p * (dp[r] - stats[64 + qi]);
+      for (int g = 0; g < 4; ++g) {
+        const float4 l4 = *reinterpret_cast<const float4*>(stats + i * 32 + g * 8 + 4 * kc);
+        const float4 d4 = *reinterpret_cast<const float4*>(stats + 64 + i * 32 + g * 8 + 4 * kc);
+        const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * g + e;
+          float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -ls[e]));
+          if (edge) {
+            const int q = qs + g * 8 + 4 * kc + e;
+            if (my_kv >= kv_len || q >= S || (sh.causal && my_kv > q)) p = 0.f;
+          }
+          sc[r] = p;
+          dp[r] = p * (dp[r] - ds[e]);
+        }
       }
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const bf16x8_t pf = pack8(sc, h), dsf = pack8(dp, h);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-          dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(dtile, i * 32 + 16 * h, t, lane), pf, dv[t], 0, 0, 0);
-          dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(qtile, i * 32 + 16 * h, t, lane), dsf, dk[t], 0, 0, 0);
+          dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(dtile, ft_base, i * 32 + 16 * h, t), pf, dv[t], 0, 0, 0);
+          dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(qtile, ft_base, i * 32 + 16 * h, t), dsf, dk[t], 0, 0, 0);
         }
       }
     }
-    if (qt + 1 < q_tiles) store_tile(stage ^ 1);
-    __syncthreads();
-  }
+  };
+  SLAPO_TILE_PIPELINE(n_tiles, DKV_LOAD, DKV_STORE, compute);
+#undef DKV_LOAD
+#undef DKV_STORE
+
   if (my_kv < S) {
     bf16_t* krow = dqkv + ((int64_t)b * S + my_kv) * rs + H + a * D;
     bf16_t* vrow = krow + H;
@@ -379,10 +407,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
                                                                const float* __restrict__ delta,
                                                                bf16_t* __restrict__ dqkv) {
   constexpr int NS = D / 16, NT = D / 32;
+  constexpr int TE = Tile<D>::ELEMS;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int S = sh.seq, H = sh.hidden;
   const int b = blockIdx.z, a = blockIdx.y, q_base = blockIdx.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
+  const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
   const int64_t rs = 3 * (int64_t)H;
   const bf16_t* base = qkv + (int64_t)b * S * rs + a * D;
   const int kv_len = visible_keys(sh, seqlens, b);
@@ -391,7 +421,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
   const int n_tiles = (kv_end + 63) / 64;
   const int my_q = q_base + 32 * wave + (lane & 31);
   const int q_ld = my_q < S ? my_q : S - 1;
-  const int wave_q_max = q_base + 32 * wave + 31;
+  const int wave_q_min = q_base + 32 * wave, wave_q_max = wave_q_min + 31;
   const float scale = rsqrtf((float)D), sl2 = LOG2E * scale;
 
   bf16x8_t qf[NS], df[NS];
@@ -408,56 +438,47 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[t][r] = 0.f;
 
-  TileMover<D> mk, mv;
-  if (n_tiles > 0) {
-    mk.load(base + H, rs, 0, S - 1, tid, S);
-    mv.load(base + 2 * H, rs, 0, S - 1, tid, S);
-    mk.store(smem, tid);
-    mv.store(smem + 64 * D, tid);
-  }
-  __syncthreads();
-  for (int it = 0; it < n_tiles; ++it) {
+  TileRegs<D> rk[2], rv[2];
+#define DQ_LOAD(set, t) do { rk[set].load(base + H, rs, (t) * 64, S - 1, tid); rv[set].load(base + 2 * H, rs, (t) * 64, S - 1, tid); } while (0)
+#define DQ_STORE(stage, set) do { rk[set].store(smem + (stage) * 2 * TE, tid); rv[set].store(smem + (stage) * 2 * TE + TE, tid); } while (0)
+  auto compute = [&](int stage, int it) {
     const int kv0 = it * 64;
-    const bf16_t* kt = smem + (it & 1) * 128 * D;
-    const bf16_t* vt = kt + 64 * D;
-    if (it + 1 < n_tiles) {
-      mk.load(base + H, rs, kv0 + 64, S - 1, tid, S);
-      mv.load(base + 2 * H, rs, kv0 + 64, S - 1, tid, S);
-    }
-    if (!sh.causal || kv0 <= wave_q_max) {
+    if (sh.causal && kv0 > wave_q_max) return;
+    const bf16_t* kt = smem + stage * 2 * TE;
+    const bf16_t* vt = kt + TE;
+    const bool edge = (kv0 + 64 > kv_len) || (sh.causal && kv0 + 63 > wave_q_min);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        f32x16_t sc, dp;
+    for (int i = 0; i < 2; ++i) {
+      f32x16_t sc, dp;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
+      for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(kt, i * 32, s, lane), qf[s], sc, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(vt, i * 32, s, lane), df[s], dp, 0, 0, 0);
-        }
+      for (int s = 0; s < NS; ++s) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(kt, fr_base, i * 32, s), qf[s], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(vt, fr_base, i * 32, s), df[s], dp, 0, 0, 0);
+      }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -my_lse2));
+        if (edge) {
           const int kv = kv0 + i * 32 + acc_row(r, lane);
-          float p = __builtin_amdgcn_exp2f(sc[r] * sl2 - my_lse2);
           if (kv >= kv_len || (sh.causal && kv > my_q)) p = 0.f;
-          dp[r] = p * (dp[r] - my_delta);
         }
+        dp[r] = p * (dp[r] - my_delta);
+      }
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const bf16x8_t dsf = pack8(dp, h);
+      for (int h = 0; h < 2; ++h) {
+        const bf16x8_t dsf = pack8(dp, h);
 #pragma unroll
-          for (int t = 0; t < NT; ++t)
-            dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(kt, i * 32 + 16 * h, t, lane), dsf, dq[t], 0, 0, 0);
-        }
+        for (int t = 0; t < NT; ++t)
+          dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(kt, ft_base, i * 32 + 16 * h, t), dsf, dq[t], 0, 0, 0);
       }
     }
-    if (it + 1 < n_tiles) {
-      bf16_t* nk = smem + ((it + 1) & 1) * 128 * D;
-      mk.store(nk, tid);
-      mv.store(nk + 64 * D, tid);
-    }
-    __syncthreads();
-  }
+  };
+  SLAPO_TILE_PIPELINE(n_tiles, DQ_LOAD, DQ_STORE, compute);
+#undef DQ_LOAD
+#undef DQ_STORE
+
   if (my_q < S) {
     bf16_t* qrow = dqkv + ((int64_t)b * S + my_q) * rs + a * D;
 #pragma unroll
@@ -601,7 +622,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_simple_kernel(AttnShape sh,
 // =================================== launchers ===================================================
 template <int D>
 static void fwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens, void* out, float* lse, hipStream_t st) {
-  const size_t lds = (size_t)2 * 128 * D * sizeof(bf16_t);
+  const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
   auto kern = attn_fwd_bf16_kernel<D>;
   (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3((s.seq + 127) / 128, s.heads, s.batch), dim3(256), lds, st, s, (const bf16_t*)qkv,
@@ -631,14 +652,14 @@ static void bwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens
                      (const bf16_t*)out, (const bf16_t*)dout, delta);
   dim3 grid((s.seq + 127) / 128, s.heads, s.batch);
   {
-    const size_t lds = (size_t)2 * (128 * D + 256) * sizeof(bf16_t);
+    const size_t lds = (size_t)2 * (2 * Tile<D>::ELEMS + 256) * sizeof(bf16_t);
     auto kern = attn_bwd_dkdv_bf16_kernel<D>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)dout, lse,
                        (const float*)delta, (bf16_t*)dqkv);
   }
   {
-    const size_t lds = (size_t)2 * 128 * D * sizeof(bf16_t);
+    const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
     auto kern = attn_bwd_dq_bf16_kernel<D>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)dout, lse,
