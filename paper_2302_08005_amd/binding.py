@@ -8,7 +8,7 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libslapo_mi355x.so")
+LIB_PATH = os.environ.get("SLAPO_LIB", os.path.join(HERE, "libslapo_mi355x.so"))
 
 BF16, FP32 = 0, 1
 GELU, RELU = 0, 1

@@ -222,12 +222,12 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
     launch_gemm(f32, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, st);
   };
-  auto reduce_rows = [&](int which, void* out) {
-    launch_colreduce_partials(f32, nrow, 3 * (int64_t)H, H, prow + (size_t)which * H, out, acc, st);
-  };
   auto colsum = [&](const void* a, int N, void* out) {
     launch_colsum_partials(f32, T, N, a, pcol, st);
     launch_colreduce_partials(f32, ncol, N, N, pcol, out, acc, st);
+  };
+  auto reduce_rows = [&](void* dgamma, void* dbeta, void* dbias) {
+    launch_colreduce3(f32, nrow, H, prow, dgamma, dbeta, dbias, acc, st);
   };
 
   // ---- FFN block ----
@@ -235,10 +235,9 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     launch_bdrln_bwd(f32, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, st);
   } else {
     launch_bdrln_bwd(f32, T, H, dy, sv + L.z2, mu2, rstd2, p->ln2_g, nullptr, t0, t1, prow, dp1, st);
-    reduce_rows(0, gr->ln2_g);
-    reduce_rows(1, gr->ln2_b);
   }
-  reduce_rows(2, gr->b2);
+  if (d->pre_ln) reduce_rows(nullptr, nullptr, gr->b2);
+  else reduce_rows(gr->ln2_g, gr->ln2_b, gr->b2);
   launch_gemm(f32, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
   dweight(H, F, t1, g, gr->w2);
   colsum(du, F, gr->b1);
@@ -248,14 +247,11 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   // ---- attention block ----
   if (d->pre_ln) {
     launch_bdrln_bwd(f32, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t1, prow, dp0, st);
-    reduce_rows(0, gr->ln2_g);
-    reduce_rows(1, gr->ln2_b);
+    reduce_rows(gr->ln2_g, gr->ln2_b, gr->bo);
   } else {
     launch_bdrln_bwd(f32, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t1, prow, dp0, st);
-    reduce_rows(0, gr->ln1_g);
-    reduce_rows(1, gr->ln1_b);
+    reduce_rows(gr->ln1_g, gr->ln1_b, gr->bo);
   }
-  reduce_rows(2, gr->bo);
   launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, H, t1, p->wo, t0, nullptr, nullptr, nullptr, st);
   dweight(H, H, t1, attn, gr->wo);
   launch_attn_bwd(f32, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
@@ -264,8 +260,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     dweight(3 * H, H, dqkv, sv + L.n1, gr->wqkv);
     launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, 3 * H, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
     launch_bdrln_bwd(f32, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, st);
-    reduce_rows(0, gr->ln1_g);
-    reduce_rows(1, gr->ln1_b);
+    reduce_rows(gr->ln1_g, gr->ln1_b, nullptr);
   } else {
     dweight(3 * H, H, dqkv, x, gr->wqkv);
     launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);

@@ -32,6 +32,9 @@ void launch_colsum_partials(int dtype_fp32, int64_t rows, int64_t N, const void*
                             hipStream_t st);
 void launch_colreduce_partials(int dtype_fp32, int64_t nblk, int64_t stride, int64_t N, const float* partials,
                                void* out, int accumulate, hipStream_t st);
+// out_k[n] (+)= sum_i partials[(i*3 + k)*H + n] for k = 0..2 in one launch; null outputs are skipped
+void launch_colreduce3(int dtype_fp32, int64_t nblk, int H, const float* partials, void* out0, void* out1, void* out2,
+                       int accumulate, hipStream_t st);
 void launch_dropout_mask(int64_t n_elements, uint8_t* mask, const DropoutParams& dp, hipStream_t st);
 
 }  // namespace slapo

@@ -365,6 +365,49 @@ void launch_colreduce_partials(int dtype_fp32, int64_t nblk, int64_t stride, int
   else hipLaunchKernelGGL(colreduce_partials_kernel<bf16_t>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (bf16_t*)out, accumulate);
 }
 
+// the three partial rows (dgamma, dbeta, dbias) of the fused backward kernel in one launch
+template <typename T>
+__global__ __launch_bounds__(1024) void colreduce3_kernel(int64_t nblk, int H, const float* __restrict__ partials,
+                                                          T* out0, T* out1, T* out2, int accumulate) {
+  __shared__ float red[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, which = blockIdx.y;
+  T* out = which == 0 ? out0 : (which == 1 ? out1 : out2);
+  if (out == nullptr) return;   // uniform for the block
+  const int64_t n = (int64_t)blockIdx.x * 64 + lane;
+  const int64_t per = (nblk + 15) / 16;
+  const int64_t i0 = wave * per, i1 = (i0 + per < nblk) ? i0 + per : nblk;
+  const float* src = partials + (int64_t)which * H;
+  const int64_t stride = 3 * (int64_t)H;
+  float s = 0.f;
+  if (n < H) {
+    int64_t i = i0;
+    for (; i + 8 <= i1; i += 8) {
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = src[(i + k) * stride + n];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s += v[k];
+    }
+    for (; i < i1; ++i) s += src[i * stride + n];
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && n < H) {
+    float t = red[0][lane];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) t += red[w][lane];
+    if (accumulate) t += to_f32(out[n]);
+    from_f32(out[n], t);
+  }
+}
+
+void launch_colreduce3(int dtype_fp32, int64_t nblk, int H, const float* partials, void* out0, void* out1, void* out2,
+                       int accumulate, hipStream_t st) {
+  dim3 grid((unsigned)((H + 63) / 64), 3);
+  if (dtype_fp32) hipLaunchKernelGGL(colreduce3_kernel<float>, grid, dim3(1024), 0, st, nblk, H, partials, (float*)out0, (float*)out1, (float*)out2, accumulate);
+  else hipLaunchKernelGGL(colreduce3_kernel<bf16_t>, grid, dim3(1024), 0, st, nblk, H, partials, (bf16_t*)out0, (bf16_t*)out1, (bf16_t*)out2, accumulate);
+}
+
 void launch_dropout_mask(int64_t n_elements, uint8_t* mask, const DropoutParams& dp, hipStream_t st) {
   const int64_t nb = n_elements / 8;
   hipLaunchKernelGGL(dropout_mask_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, nb, mask, dp);
