@@ -21,6 +21,9 @@ import workloads as W
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (figures and commands in profiles/); None where no counter run has been made.
+TRAFFIC_BYTES_PER_LAUNCH = {}
 
 
 def layer_flops(cfg, seqlens):
@@ -69,6 +72,8 @@ def main():
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is design-only.",
@@ -92,6 +97,11 @@ def main():
         B.slapo_layer_fwd(layer.desc, layer.params, xd, sld, y, layer.saved, layer.scratch)
         B.slapo_layer_bwd(layer.desc, layer.params, xd, sld, dyd, layer.saved, dx, layer.grads, layer.scratch)
 
+    if args.calibrate_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -111,8 +121,31 @@ def main():
     T, H, F = cfg.tokens, cfg.hidden, cfg.ffn
     dt, act = cfg.dtype, cfg.act
 
-    # dominant kernel: the FFN1 forward GEMM with the fused bias+activation epilogue, launched exactly as in
-    # the layer (same shapes, same tile selection), timed alone with events on the launch stream
+    # Dominant kernel: the weight-gradient (TN) GEMM kernel. One kernel symbol serves dW2 = dR2^T G,
+    # dW1 = dU^T Y1 and dWqkv = dQKV^T X (three launches per step, the largest share of the step in the
+    # rocprofv3 trace). The three launches are repeated here exactly as the layer issues them (same shapes,
+    # same tile selection), alone on the launch stream between HIP events.
+    tdt = xd.dtype
+    mk = lambda *shape: torch.randn(*shape, device="cuda", dtype=torch.float32).to(tdt)
+    tn_shapes = [(H, F, T), (F, H, T), (3 * H, H, T)]          # (M, N, K): C[M,N] = A[K,M]^T B[K,N]
+    tn_bufs = [(mk(K, M), mk(K, N), torch.empty(M, N, device="cuda", dtype=tdt)) for (M, N, K) in tn_shapes]
+
+    def dominant():
+        for (M, N, K), (a, b, c) in zip(tn_shapes, tn_bufs):
+            B.slapo_gemm(dt, B.TN, B.EPI_NONE, act, M, N, K, a, b, c)
+
+    for _ in range(5):
+        dominant()
+    reps = max(20, args.steps)
+    dom_ms = event_time_ms(dominant, reps, stream) / len(tn_shapes)      # average per launch
+    dom_flops = sum(2.0 * M * N * K for (M, N, K) in tn_shapes) / len(tn_shapes)
+    achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<TN,128,128,64,...> (weight gradients dW2, dW1, dWqkv)",
+                "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
+                "avg_launch_us": dom_ms * 1e3, "flop_per_launch": dom_flops}
+
+    # for reference: the largest forward GEMM with its fused bias+activation epilogue (FFN1)
     y1 = layer.saved_tensor("n2" if cfg.pre_ln else "y1")
     u = layer.saved_tensor("u")
     g = torch.empty_like(u)
@@ -122,12 +155,8 @@ def main():
 
     for _ in range(5):
         ffn1()
-    ffn1_ms = event_time_ms(ffn1, max(20, args.steps), stream)
-    ffn1_flops = 2.0 * T * F * H
-    achieved = ffn1_flops / (ffn1_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<NT,bias+act> (FFN1 forward)", "achieved": achieved,
-                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": None, "avg_launch_us": ffn1_ms * 1e3}
+    ffn1_ms = event_time_ms(ffn1, reps, stream)
+    ffn1_tf = 2.0 * T * F * H / (ffn1_ms * 1e-3) / 1e12
 
     # the HBM-bound fused epilogue (bias+dropout+residual+LayerNorm forward), algorithmic bytes 4*T*H*eb
     eb = 4 if cfg.dtype == W.FP32 else 2
@@ -146,7 +175,10 @@ def main():
     epi_ms = event_time_ms(epi, max(20, args.steps), stream)
     epi_gbs = 4.0 * T * H * eb / (epi_ms * 1e-3) / 1e9
 
-    extra = {"layer_tflops": total_flops / (ms * 1e-3) / 1e12,
+    extra = {"ffn1_fwd_gemm_bias_act": {"bound": "mfma", "achieved": ffn1_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                        "unit": "TFLOP/s", "frac": ffn1_tf / MFMA_BF16_PEAK_TFLOPS,
+                                        "avg_launch_us": ffn1_ms * 1e3},
+             "layer_tflops": total_flops / (ms * 1e-3) / 1e12,
              "layer_frac_of_mfma_peak": total_flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
              "gpu_event_ms_per_step": gpu_ms, "wall_ms_per_step": wall_ms,
              "epilogue_bdrln_fwd": {"bound": "hbm", "achieved": epi_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",

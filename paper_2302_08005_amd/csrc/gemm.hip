@@ -59,8 +59,8 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
 //    2*BK + 16 bytes puts them in 16 different bank groups.
 //  - M-contiguous tile [BK][rows]: 16 lanes read 4 consecutive k-rows x 32 B; a pitch of 2*rows + 32 bytes
 //    keeps the four rows apart.
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int PF, bool KTAIL, int EPI>
-__global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(int M, int N, int K,
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, bool KTAIL, int EPI>
+__global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, int N, int K,
                                                                   const bf16_t* __restrict__ A,
                                                                   const bf16_t* __restrict__ B,
                                                                   bf16_t* __restrict__ C,
@@ -69,7 +69,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(int M, int N,
                                                                   bf16_t* __restrict__ aux_out, int act) {
   constexpr bool A_KC = (LAYOUT != GEMM_TN);  // A operand contiguous along K
   constexpr bool B_KC = (LAYOUT == GEMM_NT);
-  constexpr int NTHR = WGM * WGN * 64;
+  // KS == 2: two sets of WGM x WGN wavefronts share the output tile; set g multiplies the g-th half of
+  // every K slab and the two accumulator sets are added through LDS before the epilogue. This doubles the
+  // wavefronts per SIMD without shrinking the per-wave tile (LDS traffic per flop stays that of the
+  // larger wave tile).
+  constexpr int NTHR = WGM * WGN * KS * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = BM * BK / 8 / NTHR, B_LOADS = BN * BK / 8 / NTHR;
   static_assert(A_LOADS >= 1 && B_LOADS >= 1, "tile too small for the thread count");
@@ -81,17 +85,25 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(int M, int N,
   bf16_t* sA = smem;            // [2][SA]
   bf16_t* sB = smem + 2 * SA;   // [2][SB]
 
-  // Workgroups are handed to the 8 XCDs round-robin; renumber them so that each XCD (own L2) works
-  // on a contiguous band of output tiles and re-reads the same operand panels.
+  // Workgroups are handed to the 8 XCDs round-robin. Renumber them so that each XCD (own L2) gets a
+  // run of consecutive tile ids, and order the ids in groups of 4 tile rows walked column by column, so
+  // that the tiles an XCD works on at the same time form a compact block: its workgroups walk K in step,
+  // and every A (B) slab that reaches the L2 is used by all tiles of its row (column) in the block.
   const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
   const int nblk = tiles_m * tiles_n;
   int bid = blockIdx.x;
   const int per_xcd = nblk / 8;
   if (bid < per_xcd * 8) bid = (bid & 7) * per_xcd + (bid >> 3);
-  const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
+  constexpr int GROUP_M = 4;
+  const int group = bid / (GROUP_M * tiles_n);
+  const int first_m = group * GROUP_M;
+  const int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+  const int in_group = bid - group * GROUP_M * tiles_n;
+  const int tile_m = first_m + in_group % gsz, tile_n = in_group / gsz;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int kgroup = (tid >> 6) / (WGM * WGN), wave = (tid >> 6) % (WGM * WGN);
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
 
   // Each thread moves A_LOADS + B_LOADS 16-byte pieces per slab. Piece i of a thread sits RSA (RSB) tile
@@ -187,7 +199,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(int M, int N,
     const bf16_t* a = sA + stage * SA;
     const bf16_t* b = sB + stage * SB;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int kq = 0; kq < BK / 16 / KS; ++kq) {
+      const int ks = kq + kgroup * (BK / 16 / KS);
       bf16x8_t fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) fa[i] = frag(a, std::integral_constant<bool, A_KC>{}, fa_base, PA, i, ks);
@@ -234,6 +247,28 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(int M, int N,
   // lane%32) go, one 32-row slab at a time, through a per-wave fp32 staging area in LDS so that every
   // global access of the epilogue (bias, auxiliary input, both outputs) is a 16-byte access of 8
   // consecutive columns of one row. The main loop ended with a barrier, so the stages are free.
+  if (KS == 2) {   // add the second wave set's accumulators to the first; then only the first goes on
+    float* red = reinterpret_cast<float*>(smem) + wave * (TM * TN * 16 * 64) + lane;
+    if (kgroup == 1) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) red[((i * TN + j) * 16 + r) * 64] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (kgroup == 0) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += red[((i * TN + j) * 16 + r) * 64];
+    }
+    __syncthreads();
+    if (kgroup == 1) return;
+  }
   constexpr int LDP = WN + 4;
   float* stage = reinterpret_cast<float*>(smem) + wave * (32 * LDP);
   constexpr int CPR = WN / 8;         // 8-column chunks per staged row
@@ -288,14 +323,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(int M, int N,
   }
 }
 
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN>
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS>
 constexpr size_t gemm_lds_bytes() {
   constexpr bool A_KC = (LAYOUT != GEMM_TN), B_KC = (LAYOUT == GEMM_NT);
   constexpr size_t SA = A_KC ? BM * (BK + 8) : BK * (BM + 16);
   constexpr size_t SB = B_KC ? BN * (BK + 8) : BK * (BN + 16);
   constexpr size_t main_bytes = 2 * (SA + SB) * sizeof(bf16_t);
   constexpr size_t epi_bytes = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
-  return main_bytes > epi_bytes ? main_bytes : epi_bytes;
+  constexpr size_t red_bytes = KS == 2 ? (size_t)BM * BN * sizeof(float) : 0;
+  constexpr size_t m1 = main_bytes > epi_bytes ? main_bytes : epi_bytes;
+  return m1 > red_bytes ? m1 : red_bytes;
 }
 
 // fp32 correctness kernel: 64x64 tile, 16-deep slabs, each thread a 4x4 block.
@@ -349,21 +386,21 @@ constexpr bool epi_used(int layout, int epi) {
                            : (epi == EPI_NONE || epi == EPI_ADD);
 }
 
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int PF, bool KTAIL>
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, bool KTAIL>
 static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                              const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const size_t lds = gemm_lds_bytes<LAYOUT, BM, BN, BK, WGM, WGN>();
+  const size_t lds = gemm_lds_bytes<LAYOUT, BM, BN, BK, WGM, WGN, KS>();
 #define SLAPO_GEMM(E)                                                                                       \
   do {                                                                                                      \
     if constexpr (KTAIL || epi_used(LAYOUT, E)) {                                                           \
-      auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, BK, WGM, WGN, PF, KTAIL, E>;                             \
+      auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, BK, WGM, WGN, KS, PF, KTAIL, E>;                             \
       (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
-      hipLaunchKernelGGL(kern, dim3(tiles), dim3(WGM * WGN * 64), lds, st, M, N, K, (const bf16_t*)A,       \
+      hipLaunchKernelGGL(kern, dim3(tiles), dim3(WGM * WGN * KS * 64), lds, st, M, N, K, (const bf16_t*)A,       \
                          (const bf16_t*)B, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)aux_in,          \
                          (bf16_t*)aux_out, act);                                                            \
     } else {                                                                                                \
-      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in,       \
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in,       \
                                                            aux_out, st);                                    \
     }                                                                                                       \
   } while (0)
@@ -379,21 +416,22 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 
 // Tile selection, from measurements on the layer's shapes: 256x256 tiles (8 wavefronts, 128x64 each) when
 // they still cover at least three quarters of the 256 CUs; otherwise 128x128 (8 wavefronts, 64x32 each);
-// for outputs with few tiles 128x64 tiles with 128-deep slabs. All use two slabs of register prefetch,
-// which needs an even number of whole slabs; other K go to the general kernel (one slab, zero-filled tail).
+// for outputs with few tiles 128x64 tiles with 128-deep slabs and two wave sets splitting each slab. All
+// use two slabs of register prefetch, which needs an even number of whole slabs; other K go to the general
+// kernel (one slab, zero-filled tail).
 template <int LAYOUT>
 static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                         const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
   if (K % 128 == 0 && t256 >= 192)
-    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 128 == 0 && (t128 >= 160 || K % 256 != 0))
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 256 == 0)
-    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
 }
 
 void launch_gemm(int dtype_fp32, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
