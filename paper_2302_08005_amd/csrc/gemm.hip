@@ -30,6 +30,30 @@ __device__ __forceinline__ float act_grad(float u, int act) {
   return cdf + u * pdf;
 }
 
+// GeLU for the bf16 epilogues. Phi(u) = 0.5 (1 + erf(u / sqrt 2)) with the erf of Abramowitz & Stegun 7.1.26
+// (|error| <= 1.5e-7, far below one bf16 rounding): for x >= 0, erf(x) = 1 - t (a1 + t (a2 + ... a5 t)) exp(-x^2),
+// t = 1 / (1 + 0.3275911 x). Written for h = 0.5 * poly * exp(-u^2/2): Phi(-|u|) = h, Phi(|u|) = 1 - h, so the
+// negative tail has no cancellation. One exp2, one reciprocal and a dozen FMAs, about half the cost of erff.
+struct GeluTerms { float phi, e; };   // Phi(u) and exp(-u^2 / 2)
+__device__ __forceinline__ GeluTerms gelu_terms(float u) {
+  const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(u), 0.3275911f * 0.70710678118654752f, 1.0f));
+  const float e = __builtin_amdgcn_exp2f(u * u * (-0.5f * 1.4426950408889634f));
+  float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+  p = fmaf(t, p, 0.5f * 1.421413741f);
+  p = fmaf(t, p, 0.5f * -0.284496736f);
+  p = fmaf(t, p, 0.5f * 0.254829592f);
+  const float h = p * t * e;
+  GeluTerms g;
+  g.phi = u < 0.f ? h : 1.0f - h;
+  g.e = e;
+  return g;
+}
+__device__ __forceinline__ float gelu_fast(float u) { return u * gelu_terms(u).phi; }
+__device__ __forceinline__ float gelu_grad_fast(float u) {
+  const GeluTerms g = gelu_terms(u);
+  return fmaf(u * g.e, 0.39894228040143268f, g.phi);
+}
+
 template <typename T>
 __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int64_t m, int64_t n, int64_t ldc,
                                                T* __restrict__ C, const T* __restrict__ bias,
@@ -304,13 +328,23 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
           for (int e = 0; e < 8; ++e) v[e] += bv[e];
           store8(aux_out + idx, v);
           // activation of the stored (rounded) pre-activation, the value backward will differentiate at
+          if (act == ACT_RELU) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = act_fwd(bf16_to_f32(f32_to_bf16(v[e])), act);
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = gelu_fast(bf16_to_f32(f32_to_bf16(v[e])));
+          }
         } else if (EPI == EPI_DACT) {
           float u[8];
           load8(aux_in + idx, u);
+          if (act == ACT_RELU) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] *= act_grad(u[e], act);
+            for (int e = 0; e < 8; ++e) v[e] = u[e] > 0.f ? v[e] : 0.f;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(u[e]);
+          }
         } else if (EPI == EPI_ADD) {
           float u[8];
           load8(aux_in + idx, u);
