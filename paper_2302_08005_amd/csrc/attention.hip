@@ -183,7 +183,8 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int kv = kv0 + i * 32 + acc_row(r, lane);
-          if (kv >= kv_len || (sh.causal && kv > my_q)) sc[i][r] = -INFINITY;
+          const bool hide = (kv >= kv_len) | ((sh.causal != 0) & (kv > my_q));
+          sc[i][r] = hide ? -INFINITY : sc[i][r];
         }
     }
     float mx = -INFINITY;
@@ -322,14 +323,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
   TileRegs<D> rq[2], rd[2];
   float aux[2] = {0.f, 0.f};
   const int stat_row = tid & 63;
+  // threads 0..63 carry lse, threads 64..127 delta, threads 128..255 duplicate them (same values to the same
+  // slots, so no thread is special). The value is only touched when it is stored to LDS a step later, so
+  // the load stays in flight like the tile loads.
+  const float* stat_src = (tid & 127) < 64 ? lse_row : delta_row;
+  const float stat_mul = (tid & 127) < 64 ? LOG2E : 1.0f;
   auto load_stats = [&](int q0) -> float {
     int q = q0 + stat_row;
     q = q < S ? q : S - 1;
-    // threads 0..63 carry lse (in log2 units), threads 64..127 delta; the others re-read delta and drop it
-    return tid < 64 ? lse_row[q] * LOG2E : delta_row[q];
+    return stat_src[q];
   };
 #define DKV_LOAD(set, t) do { const int q0_ = (q_first + (t)) * 64; rq[set].load(base, rs, q0_, S - 1, tid); rd[set].load(dobase, H, q0_, S - 1, tid); aux[set] = load_stats(q0_); } while (0)
-#define DKV_STORE(stage, set) do { bf16_t* t0_ = smem + (stage) * STAGE; rq[set].store(t0_, tid); rd[set].store(t0_ + TE, tid); if (tid < 128) reinterpret_cast<float*>(t0_ + 2 * TE)[tid] = aux[set]; } while (0)
+#define DKV_STORE(stage, set) do { bf16_t* t0_ = smem + (stage) * STAGE; rq[set].store(t0_, tid); rd[set].store(t0_ + TE, tid); reinterpret_cast<float*>(t0_ + 2 * TE)[tid & 127] = aux[set] * stat_mul; } while (0)
   auto compute = [&](int stage, int it) {
     const int q0 = (q_first + it) * 64;
     const bf16_t* qtile = smem + stage * STAGE;
@@ -357,9 +362,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
           float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -ls[e]));
-          if (edge) {
+          if (edge) {   // uniform for the wavefront; the per-lane part is a select, not a branch
             const int q = qs + g * 8 + 4 * kc + e;
-            if (my_kv >= kv_len || q >= S || (sh.causal && my_kv > q)) p = 0.f;
+            const bool hide = (my_kv >= kv_len) | (q >= S) | ((sh.causal != 0) & (my_kv > q));
+            p = hide ? 0.f : p;
           }
           sc[r] = p;
           dp[r] = p * (dp[r] - ds[e]);
@@ -402,9 +408,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                                const int32_t* __restrict__ seqlens,
+                                                               const bf16_t* __restrict__ out,
                                                                const bf16_t* __restrict__ dout,
                                                                const float* __restrict__ lse,
-                                                               const float* __restrict__ delta,
+                                                               float* __restrict__ delta,
                                                                bf16_t* __restrict__ dqkv) {
   constexpr int NS = D / 16, NT = D / 32;
   constexpr int TE = Tile<D>::ELEMS;
@@ -431,7 +438,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
     df[s] = *reinterpret_cast<const bf16x8_t*>(dout + ((int64_t)b * S + q_ld) * H + a * D + 16 * s + 8 * kc);
   }
   const float my_lse2 = lse[((int64_t)b * sh.heads + a) * S + q_ld] * LOG2E;
-  const float my_delta = delta[((int64_t)b * sh.heads + a) * S + q_ld];
+  // delta = rowsum(dO * O) of this lane's query row: the lane holds half of the row's dO, lane^32 the other
+  // half. It is also written out for the dK/dV kernel, which runs after this one.
+  float my_delta = 0.f;
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    const bf16x8_t of = *reinterpret_cast<const bf16x8_t*>(out + ((int64_t)b * S + q_ld) * H + a * D + 16 * s + 8 * kc);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) my_delta = fmaf((float)of[e], (float)df[s][e], my_delta);
+  }
+  my_delta += __shfl_xor(my_delta, 32, 64);
+  if (kc == 0 && my_q < S) delta[((int64_t)b * sh.heads + a) * S + my_q] = my_delta;
   f32x16_t dq[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
@@ -462,7 +479,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
         float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -my_lse2));
         if (edge) {
           const int kv = kv0 + i * 32 + acc_row(r, lane);
-          if (kv >= kv_len || (sh.causal && kv > my_q)) p = 0.f;
+          const bool hide = (kv >= kv_len) | ((sh.causal != 0) & (kv > my_q));
+          p = hide ? 0.f : p;
         }
         dp[r] = p * (dp[r] - my_delta);
       }
@@ -647,20 +665,17 @@ void launch_attn_fwd(int dtype_fp32, const AttnShape& s, const void* qkv, const 
 template <int D>
 static void bwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens, const void* out, const void* dout,
                      const float* lse, float* delta, void* dqkv, hipStream_t st) {
-  const int64_t items = (int64_t)s.batch * s.seq * s.heads * 8;
-  hipLaunchKernelGGL((attn_delta_kernel<bf16_t, D>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, s,
-                     (const bf16_t*)out, (const bf16_t*)dout, delta);
   dim3 grid((s.seq + 127) / 128, s.heads, s.batch);
+  {  // dQ first: it also produces delta = rowsum(dO * O), which the dK/dV kernel reads
+    const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
+    auto kern = attn_bwd_dq_bf16_kernel<D>;
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)out,
+                       (const bf16_t*)dout, lse, delta, (bf16_t*)dqkv);
+  }
   {
     const size_t lds = (size_t)2 * (2 * Tile<D>::ELEMS + 256) * sizeof(bf16_t);
     auto kern = attn_bwd_dkdv_bf16_kernel<D>;
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)dout, lse,
-                       (const float*)delta, (bf16_t*)dqkv);
-  }
-  {
-    const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
-    auto kern = attn_bwd_dq_bf16_kernel<D>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)dout, lse,
                        (const float*)delta, (bf16_t*)dqkv);

@@ -94,19 +94,45 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) pg[i][j] = pb[i][j] = pd[i][j] = 0.f;
 
-  for (int64_t row = (int64_t)blockIdx.x * WAVES + wave; row < rows; row += (int64_t)gridDim.x * WAVES) {
-    const int64_t base = row * H;
-    float dy[NCH][8], xh[NCH][8];
-    float s1 = 0.f, s2 = 0.f, m = 0.f, rs = 0.f;
-    if (LN) { m = mu[row]; rs = rstd[row]; }
+  const int64_t stride = (int64_t)gridDim.x * WAVES;
+  Raw8<T> ndy[NCH], nz[NCH], nres[NCH];
+  float nm = 0.f, nrs = 0.f;
+  auto fetch = [&](int64_t r) {
+    const int64_t base = r * H;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = lane + 64 * i;
       if (c < nchunk) {
-        load8(dout + base + c * 8, dy[i]);
+        ndy[i].load(dout + base + c * 8);
+        if (LN) nz[i].load(z + base + c * 8);
+        if (dres_in) nres[i].load(dres_in + base + c * 8);
+      }
+    }
+    if (LN) { nm = mu[r]; nrs = rstd[r]; }
+  };
+  // (issuing the next row's loads ahead of the reductions was measured and made no difference)
+  for (int64_t row = (int64_t)blockIdx.x * WAVES + wave; row < rows; row += stride) {
+    fetch(row);
+    const int64_t base = row * H;
+    float dy[NCH][8], xh[NCH][8], res[NCH][8];
+    float s1 = 0.f, s2 = 0.f;
+    const float m = nm, rs = nrs;
+    Raw8<T> cz[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      if (lane + 64 * i < nchunk) {
+        ndy[i].get(dy[i]);
+        cz[i] = nz[i];
+        if (dres_in) nres[i].get(res[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
         if (LN) {
           float zz[8], g[8];
-          load8(z + base + c * 8, zz);
+          cz[i].get(zz);
           load8(gamma + c * 8, g);
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
@@ -129,10 +155,8 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) dz[j] = LN ? rs * (dy[i][j] - s1 - xh[i][j] * s2) : dy[i][j];
         if (dres_in) {
-          float e[8];
-          load8(dres_in + base + c * 8, e);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) dz[j] += e[j];
+          for (int j = 0; j < 8; ++j) dz[j] += res[i][j];
         }
         if (dz_out) store8(dz_out + base + c * 8, dz);
         if (dr_out) {
@@ -156,10 +180,9 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
       for (int i = 0; i < NCH; ++i) {
         const int c = lane + 64 * i;
         if (c < nchunk) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            slot[c * 8 + j] = pg[i][j]; slot[H + c * 8 + j] = pb[i][j]; slot[2 * H + c * 8 + j] = pd[i][j];
-          }
+          store8(slot + c * 8, pg[i]);
+          store8(slot + H + c * 8, pb[i]);
+          store8(slot + 2 * H + c * 8, pd[i]);
         }
       }
     }
@@ -170,10 +193,12 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
       for (int i = 0; i < NCH; ++i) {
         const int c = lane + 64 * i;
         if (c < nchunk) {
+          float a[8], b[8], d[8];
+          load8(slot + c * 8, a);
+          load8(slot + H + c * 8, b);
+          load8(slot + 2 * H + c * 8, d);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            pg[i][j] += slot[c * 8 + j]; pb[i][j] += slot[H + c * 8 + j]; pd[i][j] += slot[2 * H + c * 8 + j];
-          }
+          for (int j = 0; j < 8; ++j) { pg[i][j] += a[j]; pb[i][j] += b[j]; pd[i][j] += d[j]; }
         }
       }
     }
@@ -197,7 +222,7 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partials_kernel(int64_t rows, int64_t N, const T* __restrict__ a,
                                                               float* __restrict__ partials) {
-  __shared__ float red[8][32][8];
+  __shared__ __attribute__((aligned(16))) float red[8][32][8];
   const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
   const int64_t chunk = (int64_t)blockIdx.x * 32 + cx;
   const int64_t per = (rows + gridDim.y - 1) / gridDim.y;
@@ -211,14 +236,16 @@ __global__ __launch_bounds__(256) void colsum_partials_kernel(int64_t rows, int6
       for (int j = 0; j < 8; ++j) acc[j] += v[j];
     }
   }
-#pragma unroll
-  for (int j = 0; j < 8; ++j) red[ry][cx][j] = acc[j];
+  store8(&red[ry][cx][0], acc);
   __syncthreads();
   if (ry == 0 && chunk * 8 < N) {
 #pragma unroll
-    for (int k = 1; k < 8; ++k)
+    for (int k = 1; k < 8; ++k) {
+      float v[8];
+      load8(&red[k][cx][0], v);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[j] += red[k][cx][j];
+      for (int j = 0; j < 8; ++j) acc[j] += v[j];
+    }
     store8(partials + (int64_t)blockIdx.y * N + chunk * 8, acc);
   }
 }
