@@ -15,8 +15,13 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller, 16-byte aligned, row-major with
  *     the last index contiguous. The descriptor and the pointer tables are HOST structs.
  *   - Weights use the nn.Linear layout [out_features, in_features] (paper Fig. 3 caption).
- *   - `stream` is a hipStream_t passed as void*; all work is enqueued there, nothing synchronises,
- *     nothing is allocated or freed, no pointer is kept after the call returns.
+ *   - `stream` is a hipStream_t passed as void*; all work is ordered after what was enqueued there
+ *     before the call and before what is enqueued there afterwards; nothing synchronises with the host,
+ *     no device memory is allocated or freed, no pointer is kept after the call returns.
+ *     slapo_layer_bwd issues its weight-gradient GEMMs on one internal helper stream per device, created
+ *     on first use and kept for the life of the process, forked from and joined back into `stream` with
+ *     events (capturable in a HIP graph like any fork/join); SLAPO_SINGLE_STREAM=1 in the environment
+ *     keeps everything on `stream`. This helper stream is the only state the library holds.
  *   - Return value: SLAPO_OK (0) or a negative slapo_status. Argument checks run before the first
  *     HIP call, so they behave the same on a host without a GPU. Nothing throws or aborts.
  *   - Same inputs and seed give bitwise identical outputs (no floating-point atomics anywhere).

@@ -1,6 +1,9 @@
 // C ABI of the library: argument validation, layout of the `saved` / `scratch` buffers and the
 // sequence of kernel launches that makes up one layer forward / backward. Host code only.
+#include <stdlib.h>
 #include <string.h>
+
+#include <mutex>
 
 #include "../../include/slapo.h"
 #include "kernels.h"
@@ -43,6 +46,37 @@ DropoutParams make_dropout(const slapo_layer_desc* d, int site) {
 
 int finish() { return hipGetLastError() == hipSuccess ? SLAPO_OK : SLAPO_ERR_HIP; }
 
+// The weight-gradient GEMMs of the backward pass do not feed the data-gradient chain, and most kernels of
+// the chain leave half of each CU's LDS and wave slots free (one 128x128 tile per CU). They are therefore
+// issued on a helper stream that forks from and joins back into the caller's stream with events, so the
+// two kinds of GEMM share the CUs. One helper stream and a few events per device are created on first use
+// and kept for the life of the process (the only state the library holds). SLAPO_SINGLE_STREAM=1 in the
+// environment turns this off (debugging / A-B timing).
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t join = nullptr;
+  int state = 0;   // 0 untried, 1 ready, -1 unavailable
+};
+SideStream* side_stream() {
+  static SideStream table[16];
+  static std::mutex mu;
+  static const bool disabled = getenv("SLAPO_SINGLE_STREAM") && atoi(getenv("SLAPO_SINGLE_STREAM")) != 0;
+  if (disabled) return nullptr;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  SideStream& s = table[dev];
+  if (s.state == 0) {
+    bool ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; ok && i < 4; ++i) ok = hipEventCreateWithFlags(&s.fork[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+    s.state = ok ? 1 : -1;
+    if (!ok) (void)hipGetLastError();
+  }
+  return s.state == 1 ? &s : nullptr;
+}
+
 // byte offsets of the regions of `saved`
 struct SavedLayout {
   size_t qkv, attn, lse, z1, n1, y1, u, g, z2, mu1, rstd1, mu2, rstd2, total;
@@ -71,7 +105,7 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
 }
 
 struct ScratchLayout {
-  size_t t0, t1, t2, du, dqkv, delta, part_row, part_col, total;
+  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, total;
 };
 ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
@@ -82,6 +116,7 @@ ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   L.t0 = take(T * H * eb);
   L.t1 = take(T * H * eb);
   L.t2 = take(T * H * eb);
+  L.t3 = take(T * H * eb);
   L.du = take(T * F * eb);
   L.dqkv = take(T * 3 * H * eb);
   L.delta = take((size_t)d->batch * d->heads * d->seq * 4);
@@ -213,48 +248,59 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   const void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *u = sv + L.u, *g = sv + L.g;
   const float *lse = (const float*)(sv + L.lse), *mu1 = (const float*)(sv + L.mu1), *rstd1 = (const float*)(sv + L.rstd1);
   const float *mu2 = (const float*)(sv + L.mu2), *rstd2 = (const float*)(sv + L.rstd2);
-  void *t0 = sc + W.t0, *t1 = sc + W.t1, *t2 = sc + W.t2, *du = sc + W.du, *dqkv = sc + W.dqkv;
+  void *t0 = sc + W.t0, *t1 = sc + W.t1, *t2 = sc + W.t2, *t3 = sc + W.t3, *du = sc + W.du, *dqkv = sc + W.dqkv;
   float *delta = (float*)(sc + W.delta), *prow = (float*)(sc + W.part_row), *pcol = (float*)(sc + W.part_col);
   const AttnShape as = {d->batch, d->seq, H, d->heads, d->causal};
   const DropoutParams dp0 = make_dropout(d, 0), dp1 = make_dropout(d, 1);
   const int nrow = bdrln_bwd_blocks(T), ncol = colsum_blocks(T);
+  // `st` carries the data-gradient chain; `ws` the weight / bias gradients that hang off it
+  SideStream* side = side_stream();
+  hipStream_t ws = side ? side->stream : st;
+  auto fork = [&](int i) {   // everything issued on st so far happens before what follows on ws
+    if (side) { (void)hipEventRecord(side->fork[i], st); (void)hipStreamWaitEvent(ws, side->fork[i], 0); }
+  };
   // weight gradient: C (+)= A^T B
   auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
-    launch_gemm(f32, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, st);
+    launch_gemm(f32, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, ws);
   };
   auto colsum = [&](const void* a, int N, void* out) {
-    launch_colsum_partials(f32, T, N, a, pcol, st);
-    launch_colreduce_partials(f32, ncol, N, N, pcol, out, acc, st);
+    launch_colsum_partials(f32, T, N, a, pcol, ws);
+    launch_colreduce_partials(f32, ncol, N, N, pcol, out, acc, ws);
   };
   auto reduce_rows = [&](void* dgamma, void* dbeta, void* dbias) {
     launch_colreduce3(f32, nrow, H, prow, dgamma, dbeta, dbias, acc, st);
   };
+  // Buffers: t0 dZ2 -> dY1/dN2 -> dA -> dN1; t1 dR2 (kept for dW2); t2 dZ1; t3 dR1 (kept for dWo).
 
   // ---- FFN block ----
   if (d->pre_ln) {
     launch_bdrln_bwd(f32, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, st);
+    reduce_rows(nullptr, nullptr, gr->b2);
   } else {
     launch_bdrln_bwd(f32, T, H, dy, sv + L.z2, mu2, rstd2, p->ln2_g, nullptr, t0, t1, prow, dp1, st);
+    reduce_rows(gr->ln2_g, gr->ln2_b, gr->b2);
   }
-  if (d->pre_ln) reduce_rows(nullptr, nullptr, gr->b2);
-  else reduce_rows(gr->ln2_g, gr->ln2_b, gr->b2);
-  launch_gemm(f32, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+  fork(0);
   dweight(H, F, t1, g, gr->w2);
+  launch_gemm(f32, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+  fork(1);
   colsum(du, F, gr->b1);
   dweight(F, H, du, y1, gr->w1);
   if (d->pre_ln) launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
   else launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
   // ---- attention block ----
   if (d->pre_ln) {
-    launch_bdrln_bwd(f32, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t1, prow, dp0, st);
+    launch_bdrln_bwd(f32, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t3, prow, dp0, st);
     reduce_rows(gr->ln2_g, gr->ln2_b, gr->bo);
   } else {
-    launch_bdrln_bwd(f32, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t1, prow, dp0, st);
+    launch_bdrln_bwd(f32, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t3, prow, dp0, st);
     reduce_rows(gr->ln1_g, gr->ln1_b, gr->bo);
   }
-  launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, H, t1, p->wo, t0, nullptr, nullptr, nullptr, st);
-  dweight(H, H, t1, attn, gr->wo);
+  fork(2);
+  dweight(H, H, t3, attn, gr->wo);
+  launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
   launch_attn_bwd(f32, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
+  fork(3);
   colsum(dqkv, 3 * H, gr->bqkv);
   if (d->pre_ln) {
     dweight(3 * H, H, dqkv, sv + L.n1, gr->wqkv);
@@ -264,6 +310,10 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   } else {
     dweight(3 * H, H, dqkv, x, gr->wqkv);
     launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
+  }
+  if (side) {   // join: the caller's stream continues only after the weight gradients are complete
+    (void)hipEventRecord(side->join, ws);
+    (void)hipStreamWaitEvent(st, side->join, 0);
   }
   return finish();
 }
