@@ -76,13 +76,16 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
   from_f32(C[idx], v);
 }
 
-// LDS tiles are padded instead of XOR-swizzled so that every fragment address is a per-lane base plus a
-// compile-time offset. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte read, and
-// 16 lanes of a transposing 8-byte read, are served together.
-//  - K-contiguous tile [rows][BK]: 16 lanes read one 16-byte chunk of 16 consecutive rows; a row pitch of
-//    2*BK + 16 bytes puts them in 16 different bank groups.
-//  - M-contiguous tile [BK][rows]: 16 lanes read 4 consecutive k-rows x 32 B; a pitch of 2*rows + 32 bytes
-//    keeps the four rows apart.
+// LDS layouts. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte access, and 16
+// lanes of a transposing 8-byte read, are served together, so both the stores of a slab and the fragment
+// reads have to spread 16 lanes over all banks.
+//  - K-contiguous tile [rows][BK], unpadded, 16-byte chunk c of row r stored at chunk c ^ swz(r) with
+//    swz(r) = (r / RP) % (BK/8), RP = rows per 256 B: a store (16 lanes = 256 consecutive bytes of the
+//    tile) stays a permutation inside each row, and a fragment read (one chunk of 16 consecutive rows)
+//    lands in 16 different 16-byte bank groups. swz depends on the lane only (wave tiles start at
+//    multiples of 32 rows), so a fragment address is a per-lane base plus (2*ks ^ per-lane constant).
+//  - M-contiguous tile [BK][rows]: stores are whole rows; 16 lanes read 4 consecutive k-rows x 32 B, and a
+//    pitch of 2*rows + 32 bytes keeps the four rows apart.
 template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, bool KTAIL, int EPI>
 __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, int N, int K,
                                                                   const bf16_t* __restrict__ A,
@@ -101,8 +104,11 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = BM * BK / 8 / NTHR, B_LOADS = BN * BK / 8 / NTHR;
   static_assert(A_LOADS >= 1 && B_LOADS >= 1, "tile too small for the thread count");
-  constexpr int PA = A_KC ? BK + 8 : BM + 16;   // row pitch of the A tile in elements
-  constexpr int PB = B_KC ? BK + 8 : BN + 16;
+  static_assert(BK == 64 || BK == 128, "swizzle written for 128- and 256-byte tile rows");
+  constexpr int PA = A_KC ? BK : BM + 16;   // row pitch of the A tile in elements
+  constexpr int PB = B_KC ? BK : BN + 16;
+  constexpr int RP = 128 / BK;              // K-contiguous tile rows per 256 B
+  auto swz = [](int row) { return (row / RP) % (BK / 8); };
   constexpr int SA = A_KC ? BM * PA : BK * PA;  // elements per stage
   constexpr int SB = B_KC ? BN * PB : BK * PB;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
@@ -151,7 +157,10 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
     else { int c = n0 + bc; c = c < N ? c : N - 8; gb[i] = B + (int64_t)(br + i * RSB) * ldb + c; }
   }
   const int64_t stepA = A_KC ? BK : (int64_t)BK * lda, stepB = B_KC ? BK : (int64_t)BK * ldb;
-  const int la0 = ar * PA + ac, lb0 = br * PB + bc;
+  static_assert(!A_KC || RSA % 32 == 0, "pieces of a thread must share the swizzle");
+  static_assert(!B_KC || RSB % 32 == 0, "pieces of a thread must share the swizzle");
+  const int la0 = A_KC ? ar * PA + (((ac >> 3) ^ swz(ar)) << 3) : ar * PA + ac;
+  const int lb0 = B_KC ? br * PB + (((bc >> 3) ^ swz(br)) << 3) : br * PB + bc;
 
   const int nk = (K + BK - 1) / BK;
   u32x4_t ra0[A_LOADS], rb0[B_LOADS], ra1[A_LOADS], rb1[B_LOADS];   // register sets: slab k lives in set k % PF
@@ -203,13 +212,16 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // per-lane fragment bases (stage 0, 32-row tile 0, k-step 0)
-  const int fa_base = A_KC ? (wm0 + (lane & 31)) * PA + (lane >> 5) * 8
+  // K-contiguous: chunk 2*ks + lane/32 of row lane%32, at (2*ks + lane/32) ^ swz = (2*ks ^ fsw) with the
+  // low bit folded into the base
+  const int fsw = swz(lane & 31) & ~1;
+  const int fa_base = A_KC ? (wm0 + (lane & 31)) * PA + ((((lane >> 5) ^ swz(lane & 31)) & 1) << 3)
                            : (8 * (lane >> 5) + ((lane & 15) >> 2)) * PA + wm0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const int fb_base = B_KC ? (wn0 + (lane & 31)) * PB + (lane >> 5) * 8
+  const int fb_base = B_KC ? (wn0 + (lane & 31)) * PB + ((((lane >> 5) ^ swz(lane & 31)) & 1) << 3)
                            : (8 * (lane >> 5) + ((lane & 15) >> 2)) * PB + wn0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   auto frag = [&](const bf16_t* tile, auto kc_tag, int base, int pitch, int t, int ks) -> bf16x8_t {
     if constexpr (decltype(kc_tag)::value) {
-      return *reinterpret_cast<const bf16x8_t*>(tile + base + t * 32 * pitch + ks * 16);
+      return *reinterpret_cast<const bf16x8_t*>(tile + base + t * 32 * pitch + (((2 * ks) ^ fsw) << 3));
     } else {
       const bf16_t* p0 = tile + base + ks * 16 * pitch + t * 32;
       s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p0);
@@ -222,6 +234,8 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
   auto compute = [&](int stage) {
     const bf16_t* a = sA + stage * SA;
     const bf16_t* b = sB + stage * SB;
+    // scheduling hint for the slab: interleave the LDS reads with the MFMAs (variant chosen by measurement)
+    __builtin_amdgcn_iglp_opt(LAYOUT == GEMM_TN ? 1 : 0);
 #pragma unroll
     for (int kq = 0; kq < BK / 16 / KS; ++kq) {
       const int ks = kq + kgroup * (BK / 16 / KS);
@@ -360,8 +374,8 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
 template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS>
 constexpr size_t gemm_lds_bytes() {
   constexpr bool A_KC = (LAYOUT != GEMM_TN), B_KC = (LAYOUT == GEMM_NT);
-  constexpr size_t SA = A_KC ? BM * (BK + 8) : BK * (BM + 16);
-  constexpr size_t SB = B_KC ? BN * (BK + 8) : BK * (BN + 16);
+  constexpr size_t SA = A_KC ? BM * BK : BK * (BM + 16);
+  constexpr size_t SB = B_KC ? BN * BK : BK * (BN + 16);
   constexpr size_t main_bytes = 2 * (SA + SB) * sizeof(bf16_t);
   constexpr size_t epi_bytes = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
   constexpr size_t red_bytes = KS == 2 ? (size_t)BM * BN * sizeof(float) : 0;
