@@ -2,12 +2,12 @@
 // appendix schedule) and the eight backward products, with the bias, bias+activation, activation
 // derivative and residual-add epilogues applied to the fp32 accumulators in registers.
 //
-// bf16 path: 256 threads = 4 wavefronts in a 2x2 grid, each owning a (BM/2)x(BN/2) block of
-// v_mfma_f32_32x32x16_bf16 tiles; 64-deep K slabs are staged global -> registers -> LDS with two LDS
-// stages and one barrier per slab. Operands whose contraction index is contiguous in memory are read
-// from LDS with 16-byte reads; operands whose contraction index is the strided one (the "N" operand
-// of dY*W and both operands of dY^T*X) stay in their memory order in LDS and are read with the
-// transposing ds_read_b64_tr_b16, so no transposed copy of any tensor is ever made.
+// bf16 path: 8 wavefronts in a 2x4 grid (or 2 x 2x2 with an in-block K split), each owning a block of
+// v_mfma_f32_32x32x16_bf16 tiles. K slabs go global -> LDS by direct loads into a ring of LDS stages (or,
+// for shapes with a K tail, through registers), one barrier per slab. Operands whose contraction index is
+// contiguous in memory are read from LDS with 16-byte reads; operands whose contraction index is the
+// strided one (the "N" operand of dY*W and both operands of dY^T*X) stay in their memory order in LDS and
+// are read with the transposing ds_read_b64_tr_b16, so no transposed copy of any tensor is ever made.
 // fp32 path: a plain LDS-tiled FMA kernel (correctness mode).
 #include <type_traits>
 
@@ -76,18 +76,41 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
   from_f32(C[idx], v);
 }
 
-// LDS layouts. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte access, and 16
-// lanes of a transposing 8-byte read, are served together, so both the stores of a slab and the fragment
-// reads have to spread 16 lanes over all banks.
-//  - K-contiguous tile [rows][BK], unpadded, 16-byte chunk c of row r stored at chunk c ^ swz(r) with
-//    swz(r) = (r / RP) % (BK/8), RP = rows per 256 B: a store (16 lanes = 256 consecutive bytes of the
-//    tile) stays a permutation inside each row, and a fragment read (one chunk of 16 consecutive rows)
-//    lands in 16 different 16-byte bank groups. swz depends on the lane only (wave tiles start at
-//    multiples of 32 rows), so a fragment address is a per-lane base plus (2*ks ^ per-lane constant).
-//  - M-contiguous tile [BK][rows]: stores are whole rows; 16 lanes read 4 consecutive k-rows x 32 B, and a
-//    pitch of 2*rows + 32 bytes keeps the four rows apart.
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, bool KTAIL, int EPI>
-__global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, int N, int K,
+// LDS layouts. Every tile sits in LDS unpadded and in memory order, 16 bytes of thread t of a slab at byte
+// 16 t of the stage, so that a slab can be brought in either through registers or by the direct
+// global -> LDS loads of gfx950 (one wave-level load fills 1 KB of consecutive LDS, lane l at byte 16 l).
+// Bank conflicts are avoided by permuting, inside each tile row, which 16-byte chunk of global memory a
+// thread fetches. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte access, and 16
+// lanes of a transposing 8-byte read, are served together.
+//  - K-contiguous tile [rows][BK]: position p of row r holds chunk p ^ swzK(r), swzK(r) = (r / RP) % (BK/8),
+//    RP = rows per 256 B. A fragment read (one chunk of 16 consecutive rows) then lands in 16 different
+//    16-byte bank groups. swzK depends on the lane only (wave tiles start at multiples of 32 rows), so a
+//    fragment address is a per-lane base plus (2*ks ^ per-lane constant).
+//  - M-contiguous tile [BK][W]: position p of k-row r holds chunk p ^ (swzM(r) << 1), i.e. 32-byte granules
+//    are permuted by swzM(r) = (r / RPM) % min(W/16, 8), RPM = k-rows per 256 B. A transposing read (16
+//    lanes: 4 consecutive k-rows x 32 B) then finds its four rows in different bank groups.
+//
+// Why direct loads: a ds_write moves 64 B per clock and keeps the LDS busy meanwhile, so writing a slab
+// costs as much LDS time as reading it three times; measured on the chip, fragment reads running beside
+// register-staged stores take the sum of both times, beside direct loads the maximum.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_lds() {   // at most N vector-memory loads outstanding, LDS ops done
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
+}
+__device__ __forceinline__ void block_barrier() {        // barrier without the implied wait for all loads
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// PF: slabs of register prefetch of the register-staged path (NS == 0, two LDS stages).
+// NS: LDS stages of the direct-load path (0 = register-staged).
+// PW: extra wavefronts that do nothing but issue the direct loads (0 = every wavefront loads its share). A
+//     vector-memory instruction holds its wavefront at issue while the address unit is busy, and the 32 KB
+//     a 128x128 tile needs per slab keep that unit (64 B per clock) busy for as long as the slab's MFMAs
+//     take; with the loads on wavefronts of their own, that wait never stands in front of an MFMA.
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, int NS, int PW, bool KTAIL, int EPI>
+__global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(int M, int N, int K,
                                                                   const bf16_t* __restrict__ A,
                                                                   const bf16_t* __restrict__ B,
                                                                   bf16_t* __restrict__ C,
@@ -100,20 +123,28 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
   // every K slab and the two accumulator sets are added through LDS before the epilogue. This doubles the
   // wavefronts per SIMD without shrinking the per-wave tile (LDS traffic per flop stays that of the
   // larger wave tile).
-  constexpr int NTHR = WGM * WGN * KS * 64;
+  constexpr int NCOMP = WGM * WGN * KS * 64;         // threads that compute
+  constexpr int NTHR = PW ? PW * 64 : NCOMP;         // threads that load
+  static_assert(PW == 0 || (NS > 0 && KS == 1), "loader wavefronts belong to the direct path");
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = BM * BK / 8 / NTHR, B_LOADS = BN * BK / 8 / NTHR;
   static_assert(A_LOADS >= 1 && B_LOADS >= 1, "tile too small for the thread count");
-  static_assert(BK == 64 || BK == 128, "swizzle written for 128- and 256-byte tile rows");
-  constexpr int PA = A_KC ? BK : BM + 16;   // row pitch of the A tile in elements
-  constexpr int PB = B_KC ? BK : BN + 16;
-  constexpr int RP = 128 / BK;              // K-contiguous tile rows per 256 B
-  auto swz = [](int row) { return (row / RP) % (BK / 8); };
-  constexpr int SA = A_KC ? BM * PA : BK * PA;  // elements per stage
-  constexpr int SB = B_KC ? BN * PB : BK * PB;
+  static_assert(BK == 32 || BK == 64 || BK == 128, "swizzles written for 64- to 256-byte tile rows");
+  static_assert(!(KTAIL && NS), "a direct load cannot zero-fill the K tail");
+  static_assert(NS == 0 || NS == 2 || NS == 4, "stage count");
+  constexpr int PA = A_KC ? BK : BM;        // row pitch of the A tile in elements (unpadded)
+  constexpr int PB = B_KC ? BK : BN;
+  constexpr int SA = BM * BK, SB = BN * BK;  // elements per stage
+  constexpr int NSTG = NS ? NS : 2;
+  auto swzK = [](int row) { constexpr int RP = BK >= 128 ? 1 : 128 / BK; return (row / RP) % (BK / 8); };
+  auto swzM = [](int krow, auto width) {
+    constexpr int W = decltype(width)::value;
+    constexpr int RPM = W >= 128 ? 1 : 128 / W, MOD = W / 16 < 8 ? W / 16 : 8;
+    return (krow / RPM) % MOD;
+  };
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  bf16_t* sA = smem;            // [2][SA]
-  bf16_t* sB = smem + 2 * SA;   // [2][SB]
+  bf16_t* sA = smem;               // [NSTG][SA]
+  bf16_t* sB = smem + NSTG * SA;   // [NSTG][SB]
 
   // Workgroups are handed to the 8 XCDs round-robin. Renumber them so that each XCD (own L2) gets a
   // run of consecutive tile ids, and order the ids in groups of 4 tile rows walked column by column, so
@@ -132,37 +163,49 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
   const int tile_m = first_m + in_group % gsz, tile_n = in_group / gsz;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int kgroup = (tid >> 6) / (WGM * WGN), wave = (tid >> 6) % (WGM * WGN);
+  const int lane = threadIdx.x & 63;
+  const bool is_loader = PW ? threadIdx.x >= NCOMP : true;
+  const int tid = PW ? (is_loader ? threadIdx.x - NCOMP : 0) : threadIdx.x;   // index among the loading threads
+  const int cw = threadIdx.x >> 6;                                            // wavefront index
+  const int kgroup = cw / (WGM * WGN), wave = cw % (WGM * WGN);
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
 
-  // Each thread moves A_LOADS + B_LOADS 16-byte pieces per slab. Piece i of a thread sits RSA (RSB) tile
-  // rows below piece 0. Pieces outside M or N are read from a clamped (valid) address and never reach a
-  // stored output, so only the K tail needs zero fill; all loads are unconditional, which lets the
-  // compiler keep the next slabs' loads in flight while it waits for the oldest ones only.
+  // Each thread moves A_LOADS + B_LOADS 16-byte pieces per slab: thread t owns position t of the slab (tile
+  // row t / CA, chunk position t % CA), piece i sits NTHR positions (RSA tile rows) further. Pieces outside
+  // M or N are read from a clamped (valid) address and never reach a stored output, so only the K tail
+  // needs zero fill; all loads are unconditional, which lets the compiler keep the next slabs' loads in
+  // flight while it waits for the oldest ones only.
   constexpr int CA = A_KC ? BK / 8 : BM / 8, CB = B_KC ? BK / 8 : BN / 8;   // pieces per tile row
   constexpr int RSA = NTHR / CA, RSB = NTHR / CB;                            // tile rows between pieces
-  const int ar = tid / CA, ac = (tid % CA) * 8, br = tid / CB, bc = (tid % CB) * 8;
+  static_assert(NS != 0 || (RSA % 16 == 0 && RSB % 16 == 0), "the K-tail test assumes one column per thread");
+  const int ar = tid / CA, br = tid / CB;
+  // column (in elements) of the chunk fetched for the position in tile row r
+  auto col_a = [&](int r) {
+    return A_KC ? ((tid % CA) ^ swzK(r)) * 8 : ((tid % CA) ^ (swzM(r, std::integral_constant<int, BM>{}) << 1)) * 8;
+  };
+  auto col_b = [&](int r) {
+    return B_KC ? ((tid % CB) ^ swzK(r)) * 8 : ((tid % CB) ^ (swzM(r, std::integral_constant<int, BN>{}) << 1)) * 8;
+  };
+  const int ac = col_a(ar), bc = col_b(br);
   const int lda = A_KC ? K : M, ldb = B_KC ? K : N;
   const bf16_t* ga[A_LOADS];
   const bf16_t* gb[B_LOADS];
 #pragma unroll
   for (int i = 0; i < A_LOADS; ++i) {
-    if (A_KC) { int r = m0 + ar + i * RSA; r = r < M ? r : M - 1; ga[i] = A + (int64_t)r * lda + ac; }
-    else { int c = m0 + ac; c = c < M ? c : M - 8; ga[i] = A + (int64_t)(ar + i * RSA) * lda + c; }
+    const int tr = ar + i * RSA;
+    if (A_KC) { int r = m0 + tr; r = r < M ? r : M - 1; ga[i] = A + (int64_t)r * lda + col_a(tr); }
+    else { int c = m0 + col_a(tr); c = c < M ? c : M - 8; ga[i] = A + (int64_t)tr * lda + c; }
   }
 #pragma unroll
   for (int i = 0; i < B_LOADS; ++i) {
-    if (B_KC) { int r = n0 + br + i * RSB; r = r < N ? r : N - 1; gb[i] = B + (int64_t)r * ldb + bc; }
-    else { int c = n0 + bc; c = c < N ? c : N - 8; gb[i] = B + (int64_t)(br + i * RSB) * ldb + c; }
+    const int tr = br + i * RSB;
+    if (B_KC) { int r = n0 + tr; r = r < N ? r : N - 1; gb[i] = B + (int64_t)r * ldb + col_b(tr); }
+    else { int c = n0 + col_b(tr); c = c < N ? c : N - 8; gb[i] = B + (int64_t)tr * ldb + c; }
   }
   const int64_t stepA = A_KC ? BK : (int64_t)BK * lda, stepB = B_KC ? BK : (int64_t)BK * ldb;
-  static_assert(!A_KC || RSA % 32 == 0, "pieces of a thread must share the swizzle");
-  static_assert(!B_KC || RSB % 32 == 0, "pieces of a thread must share the swizzle");
-  const int la0 = A_KC ? ar * PA + (((ac >> 3) ^ swz(ar)) << 3) : ar * PA + ac;
-  const int lb0 = B_KC ? br * PB + (((bc >> 3) ^ swz(br)) << 3) : br * PB + bc;
 
   const int nk = (K + BK - 1) / BK;
+  static_assert(PF == 1 || PF == 2, "register prefetch depth");
   u32x4_t ra0[A_LOADS], rb0[B_LOADS], ra1[A_LOADS], rb1[B_LOADS];   // register sets: slab k lives in set k % PF
   // Every call issues exactly A_LOADS + B_LOADS loads (slab index clamped to the last one), so the number
   // of loads in flight is the same on every path and the oldest slab can be awaited on its own.
@@ -195,12 +238,27 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
     }
   };
   auto store_lds = [&](int stage, const u32x4_t (&ra)[A_LOADS], const u32x4_t (&rb)[B_LOADS]) {
-    bf16_t* a = sA + stage * SA + la0;
-    bf16_t* b = sB + stage * SB + lb0;
+    bf16_t* a = sA + stage * SA + tid * 8;
+    bf16_t* b = sB + stage * SB + tid * 8;
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) *reinterpret_cast<u32x4_t*>(a + i * RSA * PA) = ra[i];
+    for (int i = 0; i < A_LOADS; ++i) *reinterpret_cast<u32x4_t*>(a + i * NTHR * 8) = ra[i];
 #pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) *reinterpret_cast<u32x4_t*>(b + i * RSB * PB) = rb[i];
+    for (int i = 0; i < B_LOADS; ++i) *reinterpret_cast<u32x4_t*>(b + i * NTHR * 8) = rb[i];
+  };
+  // Direct path: the same pieces, written by the memory system straight into LDS (wave-uniform LDS base,
+  // lane l lands 16 l bytes behind it). Completion is tracked by the vector-memory counter.
+  auto load_direct = [&](int kstep, int stage) {
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    const int lw = PW ? cw - NCOMP / 64 : cw;   // index among the loading wavefronts
+    bf16_t* a = sA + stage * SA + lw * 512;
+    bf16_t* b = sB + stage * SB + lw * 512;
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + kstep * stepA), (lptr_t)(a + i * NTHR * 8), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + kstep * stepB), (lptr_t)(b + i * NTHR * 8), 16, 0, 0);
   };
 
   f32x16_t acc[TM][TN];
@@ -211,25 +269,37 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // per-lane fragment bases (stage 0, 32-row tile 0, k-step 0)
-  // K-contiguous: chunk 2*ks + lane/32 of row lane%32, at (2*ks + lane/32) ^ swz = (2*ks ^ fsw) with the
-  // low bit folded into the base
-  const int fsw = swz(lane & 31) & ~1;
-  const int fa_base = A_KC ? (wm0 + (lane & 31)) * PA + ((((lane >> 5) ^ swz(lane & 31)) & 1) << 3)
-                           : (8 * (lane >> 5) + ((lane & 15) >> 2)) * PA + wm0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const int fb_base = B_KC ? (wn0 + (lane & 31)) * PB + ((((lane >> 5) ^ swz(lane & 31)) & 1) << 3)
-                           : (8 * (lane >> 5) + ((lane & 15) >> 2)) * PB + wn0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  auto frag = [&](const bf16_t* tile, auto kc_tag, int base, int pitch, int t, int ks) -> bf16x8_t {
-    if constexpr (decltype(kc_tag)::value) {
-      return *reinterpret_cast<const bf16x8_t*>(tile + base + t * 32 * pitch + (((2 * ks) ^ fsw) << 3));
-    } else {
-      const bf16_t* p0 = tile + base + ks * 16 * pitch + t * 32;
-      s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p0);
-      s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p0 + 4 * pitch));
-      typedef short s16x8_t __attribute__((ext_vector_type(8)));
-      s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      return __builtin_bit_cast(bf16x8_t, v);
-    }
+  // Per-lane fragment addressing (stage 0, k-step 0).
+  // K-contiguous: chunk 2*ks + lane/32 of row lane%32, stored at position (2*ks + lane/32) ^ swzK =
+  // (2*ks ^ fsw) with the low bit folded into the base.
+  const int fsw = swzK(lane & 31) & ~1;
+  const int kc_low = (((lane >> 5) ^ swzK(lane & 31)) & 1) << 3;
+  const int fa_base = (wm0 + (lane & 31)) * PA + kc_low;
+  const int fb_base = (wn0 + (lane & 31)) * PB + kc_low;
+  // M-contiguous: the lane reads 4 elements at k-row krow_l (+4 for the upper half of the fragment), column
+  // 16*((lane/16)%2) + 4*(lane%4) of the 32-wide tile; the 32-byte granule index g is stored at g ^ swzM.
+  const int krow_l = 8 * (lane >> 5) + ((lane & 15) >> 2);
+  int ma_lo[2], ma_sw[2], mb_lo[2], mb_sw[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int swa = swzM(krow_l + 4 * h, std::integral_constant<int, BM>{});
+    const int swb = swzM(krow_l + 4 * h, std::integral_constant<int, BN>{});
+    ma_lo[h] = (krow_l + 4 * h) * PA + (((((lane >> 4) ^ swa) & 1)) << 4) + 4 * (lane & 3);
+    mb_lo[h] = (krow_l + 4 * h) * PB + (((((lane >> 4) ^ swb) & 1)) << 4) + 4 * (lane & 3);
+    ma_sw[h] = swa & ~1;
+    mb_sw[h] = swb & ~1;
+  }
+  auto frag_kc = [&](const bf16_t* tile, int base, int pitch, int t, int ks) -> bf16x8_t {
+    return *reinterpret_cast<const bf16x8_t*>(tile + base + t * 32 * pitch + (((2 * ks) ^ fsw) << 3));
+  };
+  auto frag_mc = [&](const bf16_t* tile, const int (&lo)[2], const int (&sw)[2], int pitch, int g0, int ks) -> bf16x8_t {
+    typedef s16x4_t __attribute__((address_space(3))) * lds4_t;
+    const bf16_t* p = tile + ks * 16 * pitch;
+    s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(p + lo[0] + ((g0 ^ sw[0]) << 4)));
+    s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(p + lo[1] + ((g0 ^ sw[1]) << 4)));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    s16x8_t v = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, v);
   };
   auto compute = [&](int stage) {
     const bf16_t* a = sA + stage * SA;
@@ -241,9 +311,11 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
       const int ks = kq + kgroup * (BK / 16 / KS);
       bf16x8_t fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = frag(a, std::integral_constant<bool, A_KC>{}, fa_base, PA, i, ks);
+      for (int i = 0; i < TM; ++i)
+        fa[i] = A_KC ? frag_kc(a, fa_base, PA, i, ks) : frag_mc(a, ma_lo, ma_sw, PA, (wm0 >> 4) + 2 * i, ks);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = frag(b, std::integral_constant<bool, B_KC>{}, fb_base, PB, j, ks);
+      for (int j = 0; j < TN; ++j)
+        fb[j] = B_KC ? frag_kc(b, fb_base, PB, j, ks) : frag_mc(b, mb_lo, mb_sw, PB, (wn0 >> 4) + 2 * j, ks);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -251,35 +323,77 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
     }
   };
 
-  // Pipeline: the slab of k-step k is computed from LDS stage k&1 while the global loads of the next PF
-  // slabs are in flight in registers (register set k % PF holds slab k); a slab is written to LDS right
-  // after the compute of the step before it. With PF == 2 the slab count must be even (the host falls
-  // back to PF == 1 otherwise). Loads and stores are issued on every step (slab index clamped; the last
-  // steps re-fetch the last slab into a stage nobody reads): with every step alike, the wait before an
-  // LDS store covers the oldest slab only and the newer loads stay in flight.
-  load_global(0, ra0, rb0);
-  if (PF > 1) load_global(1, ra1, rb1);
-  store_lds(0, ra0, rb0);
-  __syncthreads();
-  if (PF == 1) {
-    for (int k = 0; k < nk; ++k) {
-      load_global(k + 1, ra0, rb0);
-      compute(k & 1);
-      store_lds((k + 1) & 1, ra0, rb0);
-      __syncthreads();
+  if constexpr (NS == 0) {
+    // Register-staged pipeline: the slab of k-step k is computed from LDS stage k&1 while the global loads
+    // of the next PF slabs are in flight in registers (register set k % PF holds slab k); a slab is written
+    // to LDS right after the compute of the step before it. With PF == 2 the slab count must be even (the
+    // host falls back to PF == 1 otherwise). Loads and stores are issued on every step (slab index
+    // clamped; the last steps re-fetch the last slab into a stage nobody reads): with every step alike,
+    // the wait before an LDS store covers the oldest slab only and the newer loads stay in flight.
+    load_global(0, ra0, rb0);
+    if (PF > 1) load_global(1, ra1, rb1);
+    store_lds(0, ra0, rb0);
+    __syncthreads();
+    if (PF == 1) {
+      for (int k = 0; k < nk; ++k) {
+        load_global(k + 1, ra0, rb0);
+        compute(k & 1);
+        store_lds((k + 1) & 1, ra0, rb0);
+        __syncthreads();
+      }
+    } else {
+      for (int k = 0; k < nk; k += 2) {
+        load_global(k + 2, ra0, rb0);
+        compute(0);
+        store_lds(1, ra1, rb1);
+        __syncthreads();
+        load_global(k + 3, ra1, rb1);
+        compute(1);
+        store_lds(0, ra0, rb0);
+        __syncthreads();
+      }
     }
   } else {
-    for (int k = 0; k < nk; k += 2) {
-      load_global(k + 2, ra0, rb0);
-      compute(0);
-      store_lds(1, ra1, rb1);
-      __syncthreads();
-      load_global(k + 3, ra1, rb1);
-      compute(1);
-      store_lds(0, ra0, rb0);
-      __syncthreads();
+    // Direct pipeline over a ring of NS stages, slab j in stage j % NS (the slab count is a multiple of
+    // NS). Step k issues the loads of slab k + NS - 1 into the stage that step k - 1 computed from (free
+    // since the barrier that ended step k - 1), computes slab k, then waits until its own loads of slab
+    // k + 1 have landed (the younger ones stay in flight) and meets the other wavefronts at the barrier.
+    constexpr int LPS = A_LOADS + B_LOADS;   // loads per slab and loading wavefront
+    if (is_loader) {
+#pragma unroll
+      for (int j = 0; j < NS - 1; ++j) load_direct(j, j);
+    }
+    wait_loads_and_lds<(NS - 2) * LPS>();
+    block_barrier();
+    if (PW && is_loader) {
+      // loader wavefronts: issue, wait for the oldest slab, meet the others; nothing else
+      for (int k0 = 0; k0 < nk; k0 += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          const bool more = k0 + s + NS - 1 < nk;   // uniform
+          if (more) load_direct(k0 + s + NS - 1, (s + NS - 1) % NS);
+          if (more) wait_loads_and_lds<(NS - 2) * LPS>();
+          else wait_loads_and_lds<0>();
+          block_barrier();
+        }
+      }
+    } else {
+      for (int k0 = 0; k0 < nk; k0 += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          const bool more = k0 + s + NS - 1 < nk;   // uniform
+          if (!PW && more) load_direct(k0 + s + NS - 1, (s + NS - 1) % NS);
+          compute(s);
+          if (PW) wait_loads_and_lds<63>();          // LDS reads done (no loads of its own)
+          else if (more) wait_loads_and_lds<(NS - 2) * LPS>();
+          else wait_loads_and_lds<0>();
+          block_barrier();
+        }
+      }
     }
   }
+
+  if (PW && is_loader) return;   // every load has landed (the last steps drain them); the rest is compute only
 
   // Epilogue. The accumulators (element r of a 32x32 tile: row (r/4)*8 + 4*(lane/32) + r%4, column
   // lane%32) go, one 32-row slab at a time, through a per-wave fp32 staging area in LDS so that every
@@ -371,12 +485,9 @@ __global__ __launch_bounds__(WGM * WGN * KS * 64) void gemm_bf16_kernel(int M, i
   }
 }
 
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS>
+template <int BM, int BN, int BK, int WGM, int WGN, int KS, int NS>
 constexpr size_t gemm_lds_bytes() {
-  constexpr bool A_KC = (LAYOUT != GEMM_TN), B_KC = (LAYOUT == GEMM_NT);
-  constexpr size_t SA = A_KC ? BM * BK : BK * (BM + 16);
-  constexpr size_t SB = B_KC ? BN * BK : BK * (BN + 16);
-  constexpr size_t main_bytes = 2 * (SA + SB) * sizeof(bf16_t);
+  constexpr size_t main_bytes = (size_t)(NS ? NS : 2) * (BM + BN) * BK * sizeof(bf16_t);
   constexpr size_t epi_bytes = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
   constexpr size_t red_bytes = KS == 2 ? (size_t)BM * BN * sizeof(float) : 0;
   constexpr size_t m1 = main_bytes > epi_bytes ? main_bytes : epi_bytes;
@@ -434,22 +545,22 @@ constexpr bool epi_used(int layout, int epi) {
                            : (epi == EPI_NONE || epi == EPI_ADD);
 }
 
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, bool KTAIL>
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, int NS, int PW, bool KTAIL>
 static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                              const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const size_t lds = gemm_lds_bytes<LAYOUT, BM, BN, BK, WGM, WGN, KS>();
+  const size_t lds = gemm_lds_bytes<BM, BN, BK, WGM, WGN, KS, NS>();
 #define SLAPO_GEMM(E)                                                                                       \
   do {                                                                                                      \
     if constexpr (KTAIL || epi_used(LAYOUT, E)) {                                                           \
-      auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, BK, WGM, WGN, KS, PF, KTAIL, E>;                             \
+      auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, BK, WGM, WGN, KS, PF, NS, PW, KTAIL, E>;                           \
       (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
-      hipLaunchKernelGGL(kern, dim3(tiles), dim3(WGM * WGN * KS * 64), lds, st, M, N, K, (const bf16_t*)A,       \
+      hipLaunchKernelGGL(kern, dim3(tiles), dim3((WGM * WGN * KS + PW) * 64), lds, st, M, N, K, (const bf16_t*)A,       \
                          (const bf16_t*)B, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)aux_in,          \
                          (bf16_t*)aux_out, act);                                                            \
     } else {                                                                                                \
-      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in,       \
-                                                           aux_out, st);                                    \
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true>(epi, act, M, N, K, A, B, C, bias, aux_in,    \
+                                                              aux_out, st);                                 \
     }                                                                                                       \
   } while (0)
   switch (epi) {
@@ -462,24 +573,30 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 #undef SLAPO_GEMM
 }
 
-// Tile selection, from measurements on the layer's shapes: 256x256 tiles (8 wavefronts, 128x64 each) when
-// they still cover at least three quarters of the 256 CUs; otherwise 128x128 (8 wavefronts, 64x32 each);
-// for outputs with few tiles 128x64 tiles with 128-deep slabs and two wave sets splitting each slab. All
-// use two slabs of register prefetch, which needs an even number of whole slabs; other K go to the general
-// kernel (one slab, zero-filled tail).
+// Tile selection, from measurements on the layer's shapes. 256x256 tiles (8 wavefronts, 128x64 each, direct
+// loads into two stages) when they still cover at least three quarters of the 256 CUs. Otherwise 128x128
+// tiles (8 wavefronts, 64x32 each): with long K, direct loads into a ring of four stages issued by four
+// loader wavefronts; else register-staged with two slabs of prefetch. For outputs with few tiles, 128x64
+// tiles: long K the same direct scheme with four computing wavefronts, else 128-deep slabs and two wave
+// sets splitting each slab. Other K go to the general kernel (one slab of register prefetch, zero-filled
+// tail).
 template <int LAYOUT>
 static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                         const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
   if (K % 128 == 0 && t256 >= 192)
-    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 1, 2, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  else if (K % 256 == 0 && K >= 2048 && t128 >= 160)
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 1, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 128 == 0 && (t128 >= 160 || K % 256 != 0))
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 0, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  else if (K % 256 == 0 && K >= 2048)
+    launch_bf16_tile<LAYOUT, 128, 64, 64, 2, 2, 1, 1, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 256 == 0)
-    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, 0, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, true>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
 }
 
 void launch_gemm(int dtype_fp32, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,

@@ -21,7 +21,10 @@ def _dact(u, act):
     return 0.5 * (1 + erf(u / np.sqrt(2))) + u * np.exp(-0.5 * u * u) / np.sqrt(2 * np.pi)
 
 
-SHAPES = [(256, 256, 128), (296, 264, 200), (128, 128, 64), (1024, 768, 512), (520, 136, 72), (4096, 1024, 1024)]
+# the last three reach the direct-load kernels with ragged edge tiles: 128x128 tiles fed by loader wavefronts
+# (long K, one round of tiles), 256x256 tiles, and 128x64 tiles (long K, few tiles)
+SHAPES = [(256, 256, 128), (296, 264, 200), (128, 128, 64), (1024, 768, 512), (520, 136, 72), (4096, 1024, 1024),
+          (1664, 1672, 2048), (3592, 3336, 256), (520, 136, 2048)]
 
 
 @pytest.mark.parametrize("dtype", [W.BF16, W.FP32])
