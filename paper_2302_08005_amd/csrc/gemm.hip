@@ -93,6 +93,16 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
 // Why direct loads: a ds_write moves 64 B per clock and keeps the LDS busy meanwhile, so writing a slab
 // costs as much LDS time as reading it three times; measured on the chip, fragment reads running beside
 // register-staged stores take the sum of both times, beside direct loads the maximum.
+// One direct 16-byte-per-lane load: lane l of the wavefront fetches base[voffset_l + soffset ..] (bytes; zero
+// beyond `bytes`) into LDS at lds + 16 l. A plain function on purpose: the buffer builtins are only known
+// to the device pass, and a kernel template that names them directly loses its host-side launch stub.
+__device__ __forceinline__ void buffer_load_lds_16(const void* base, unsigned bytes, void* lds, unsigned voffset,
+                                                   unsigned soffset) {
+  // raw buffer resource: stride 0, size in bytes, untyped 32-bit data format; loop-invariant scalars
+  const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds, 16, voffset, soffset, 0, 0);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_loads_and_lds() {   // at most N vector-memory loads outstanding, LDS ops done
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
@@ -246,19 +256,31 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
     for (int i = 0; i < B_LOADS; ++i) *reinterpret_cast<u32x4_t*>(b + i * NTHR * 8) = rb[i];
   };
   // Direct path: the same pieces, written by the memory system straight into LDS (wave-uniform LDS base,
-  // lane l lands 16 l bytes behind it). Completion is tracked by the vector-memory counter.
+  // lane l lands 16 l bytes behind it). Completion is tracked by the vector-memory counter. The loads are
+  // buffer loads: resource = the operand from the tile's origin on, per-lane byte offset fixed for the whole
+  // K loop, the K step in the scalar offset. Issuing a slab then takes no vector-ALU instruction at all,
+  // which matters because the vector ALU is where the MFMAs run: address arithmetic of a loading wavefront
+  // queues behind the MFMAs of the wavefronts that share its SIMD (measured: 64-bit per-lane addresses make
+  // load time and MFMA time add up; this form overlaps them). Reads beyond the operand's end return zero.
+  unsigned voa[A_LOADS], vob[B_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; ++i) voa[i] = (unsigned)(((ar + i * RSA) * lda + col_a(ar + i * RSA)) * 2);
+#pragma unroll
+  for (int i = 0; i < B_LOADS; ++i) vob[i] = (unsigned)(((br + i * RSB) * ldb + col_b(br + i * RSB)) * 2);
+  const int64_t origin_a = A_KC ? (int64_t)m0 * lda : m0, origin_b = B_KC ? (int64_t)n0 * ldb : n0;
+  auto records = [](int64_t elems) { const int64_t b = elems * 2; return (unsigned)(b < 0xffffffffll ? b : 0xffffffffll); };
+  const bf16_t* base_a = A + origin_a;
+  const bf16_t* base_b = B + origin_b;
+  const unsigned bytes_a = records((int64_t)M * K - origin_a), bytes_b = records((int64_t)N * K - origin_b);
+  const int lw = __builtin_amdgcn_readfirstlane(PW ? cw - NCOMP / 64 : cw);   // index among the loading wavefronts
   auto load_direct = [&](int kstep, int stage) {
-    typedef const __attribute__((address_space(1))) void* gptr_t;
-    typedef __attribute__((address_space(3))) void* lptr_t;
-    const int lw = PW ? cw - NCOMP / 64 : cw;   // index among the loading wavefronts
     bf16_t* a = sA + stage * SA + lw * 512;
     bf16_t* b = sB + stage * SB + lw * 512;
+    const unsigned soa = (unsigned)kstep * (unsigned)(stepA * 2), sob = (unsigned)kstep * (unsigned)(stepB * 2);
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + kstep * stepA), (lptr_t)(a + i * NTHR * 8), 16, 0, 0);
+    for (int i = 0; i < A_LOADS; ++i) buffer_load_lds_16(base_a, bytes_a, a + i * NTHR * 8, voa[i], soa);
 #pragma unroll
-    for (int i = 0; i < B_LOADS; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + kstep * stepB), (lptr_t)(b + i * NTHR * 8), 16, 0, 0);
+    for (int i = 0; i < B_LOADS; ++i) buffer_load_lds_16(base_b, bytes_b, b + i * NTHR * 8, vob[i], sob);
   };
 
   f32x16_t acc[TM][TN];
@@ -575,8 +597,8 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 
 // Tile selection, from measurements on the layer's shapes. 256x256 tiles (8 wavefronts, 128x64 each, direct
 // loads into two stages) when they still cover at least three quarters of the 256 CUs. Otherwise 128x128
-// tiles (8 wavefronts, 64x32 each): with long K, direct loads into a ring of four stages issued by four
-// loader wavefronts; else register-staged with two slabs of prefetch. For outputs with few tiles, 128x64
+// tiles (8 wavefronts, 64x32 each): direct loads into a ring of four stages issued by four loader
+// wavefronts when K is a multiple of four slabs; else register-staged with two slabs of prefetch. For outputs with few tiles, 128x64
 // tiles: long K the same direct scheme with four computing wavefronts, else 128-deep slabs and two wave
 // sets splitting each slab. Other K go to the general kernel (one slab of register prefetch, zero-filled
 // tail).
@@ -586,13 +608,13 @@ static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, co
   const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
   if (K % 128 == 0 && t256 >= 192)
-    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 1, 2, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (K % 256 == 0 && K >= 2048 && t128 >= 160)
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 1, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  else if (K % 256 == 0 && t128 >= 160)
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 128 == 0 && (t128 >= 160 || K % 256 != 0))
     launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 0, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (K % 256 == 0 && K >= 2048)
-    launch_bf16_tile<LAYOUT, 128, 64, 64, 2, 2, 1, 1, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  else if (K % 256 == 0 && K >= 1024)
+    launch_bf16_tile<LAYOUT, 128, 64, 64, 2, 2, 1, 2, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 256 == 0)
     launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, 0, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else
