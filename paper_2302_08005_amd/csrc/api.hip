@@ -105,7 +105,7 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
 }
 
 struct ScratchLayout {
-  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, total;
+  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, total;
 };
 ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
@@ -123,6 +123,7 @@ ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   L.part_row = take((size_t)bdrln_bwd_blocks((int64_t)T) * 3 * H * 4);
   const size_t widest = F > 3 * H ? F : 3 * H;
   L.part_col = take((size_t)colsum_blocks((int64_t)T) * widest * 4);
+  L.part_col2 = take((size_t)colsum_blocks((int64_t)T) * widest * 4);   // the two streams of backward each own one
   L.total = o;
   return L;
 }
@@ -249,7 +250,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   const float *lse = (const float*)(sv + L.lse), *mu1 = (const float*)(sv + L.mu1), *rstd1 = (const float*)(sv + L.rstd1);
   const float *mu2 = (const float*)(sv + L.mu2), *rstd2 = (const float*)(sv + L.rstd2);
   void *t0 = sc + W.t0, *t1 = sc + W.t1, *t2 = sc + W.t2, *t3 = sc + W.t3, *du = sc + W.du, *dqkv = sc + W.dqkv;
-  float *delta = (float*)(sc + W.delta), *prow = (float*)(sc + W.part_row), *pcol = (float*)(sc + W.part_col);
+  float *delta = (float*)(sc + W.delta), *prow = (float*)(sc + W.part_row), *pcol = (float*)(sc + W.part_col), *pcol2 = (float*)(sc + W.part_col2);
   const AttnShape as = {d->batch, d->seq, H, d->heads, d->causal};
   const DropoutParams dp0 = make_dropout(d, 0), dp1 = make_dropout(d, 1);
   const int nrow = bdrln_bwd_blocks(T), ncol = colsum_blocks(T);
@@ -263,9 +264,10 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
     launch_gemm(f32, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, ws);
   };
-  auto colsum = [&](const void* a, int N, void* out) {
-    launch_colsum_partials(f32, T, N, a, pcol, ws);
-    launch_colreduce_partials(f32, ncol, N, N, pcol, out, acc, ws);
+  auto colsum = [&](const void* a, int N, void* out, hipStream_t s) {
+    float* part = s == st ? pcol2 : pcol;   // per stream, so that the two sums may run at the same time
+    launch_colsum_partials(f32, T, N, a, part, s);
+    launch_colreduce_partials(f32, ncol, N, N, part, out, acc, s);
   };
   auto reduce_rows = [&](void* dgamma, void* dbeta, void* dbias) {
     launch_colreduce3(f32, nrow, H, prow, dgamma, dbeta, dbias, acc, st);
@@ -284,7 +286,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   dweight(H, F, t1, g, gr->w2);
   launch_gemm(f32, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
   fork(1);
-  colsum(du, F, gr->b1);
+  colsum(du, F, gr->b1, ws);
   dweight(F, H, du, y1, gr->w1);
   if (d->pre_ln) launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
   else launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
@@ -301,7 +303,6 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
   launch_attn_bwd(f32, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
   fork(3);
-  colsum(dqkv, 3 * H, gr->bqkv);
   if (d->pre_ln) {
     dweight(3 * H, H, dqkv, sv + L.n1, gr->wqkv);
     launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, 3 * H, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
@@ -311,6 +312,9 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     dweight(3 * H, H, dqkv, x, gr->wqkv);
     launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
   }
+  // the last bias gradient goes behind the data gradient on the caller's stream: the helper stream's last
+  // product is the longer one, and this way the two streams end at about the same time
+  colsum(dqkv, 3 * H, gr->bqkv, st);
   if (side) {   // join: the caller's stream continues only after the weight gradients are complete
     (void)hipEventRecord(side->join, ws);
     (void)hipStreamWaitEvent(st, side->join, 0);
