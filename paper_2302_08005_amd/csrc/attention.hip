@@ -100,6 +100,21 @@ __device__ __forceinline__ int visible_keys(const AttnShape& sh, const int32_t* 
   return n;
 }
 
+// Workgroups are handed to the 8 XCDs round-robin in launch order. The 128-row blocks of one (batch, head)
+// all read that head's K and V (or Q and dO), so they are renumbered to sit on the same XCD, next to each
+// other in time, and share the tiles through its L2 instead of each fetching them from memory.
+struct BlockId { int x, a, b; };
+__device__ __forceinline__ BlockId xcd_local_block() {
+  const int nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
+  int w = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+  if (total % 8 == 0) w = (w & 7) * (total >> 3) + (w >> 3);
+  BlockId id;
+  id.x = w % nx;
+  id.a = (w / nx) % ny;
+  id.b = w / (nx * ny);
+  return id;
+}
+
 // Tile pipeline shared by the three kernels: tile t is computed from LDS stage t&1 while the loads of
 // tiles t+1 and t+2 are in flight in two register sets. Loads and stores are issued on every step with a
 // clamped tile index (the surplus ones land in a stage nobody reads), so the number of loads in flight is
@@ -135,7 +150,8 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
   constexpr int TE = Tile<D>::ELEMS;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int S = sh.seq, H = sh.hidden;
-  const int b = blockIdx.z, a = blockIdx.y, q_base = blockIdx.x * 128;
+  const BlockId blk = xcd_local_block();
+  const int b = blk.b, a = blk.a, q_base = blk.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
   const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
   const int64_t rs = 3 * (int64_t)H;
@@ -291,7 +307,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
   constexpr int STAGE = 2 * TE + 256;   // bf16 units: Q tile, dO tile, 64 lse + 64 delta floats
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int S = sh.seq, H = sh.hidden;
-  const int b = blockIdx.z, a = blockIdx.y, kv_base = blockIdx.x * 128;
+  const BlockId blk = xcd_local_block();
+  const int b = blk.b, a = blk.a, kv_base = blk.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
   const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
   const int64_t rs = 3 * (int64_t)H;
@@ -417,7 +434,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
   constexpr int TE = Tile<D>::ELEMS;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int S = sh.seq, H = sh.hidden;
-  const int b = blockIdx.z, a = blockIdx.y, q_base = blockIdx.x * 128;
+  const BlockId blk = xcd_local_block();
+  const int b = blk.b, a = blk.a, q_base = blk.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
   const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
   const int64_t rs = 3 * (int64_t)H;

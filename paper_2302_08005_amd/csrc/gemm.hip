@@ -141,7 +141,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   static_assert(A_LOADS >= 1 && B_LOADS >= 1, "tile too small for the thread count");
   static_assert(BK == 32 || BK == 64 || BK == 128, "swizzles written for 64- to 256-byte tile rows");
   static_assert(!(KTAIL && NS), "a direct load cannot zero-fill the K tail");
-  static_assert(NS == 0 || NS == 2 || NS == 4, "stage count");
+  static_assert(NS == 0 || (NS >= 2 && NS <= 10), "stage count");
   constexpr int PA = A_KC ? BK : BM;        // row pitch of the A tile in elements (unpadded)
   constexpr int PB = B_KC ? BK : BN;
   constexpr int SA = BM * BK, SB = BN * BK;  // elements per stage
@@ -376,8 +376,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
       }
     }
   } else {
-    // Direct pipeline over a ring of NS stages, slab j in stage j % NS (the slab count is a multiple of
-    // NS). Step k issues the loads of slab k + NS - 1 into the stage that step k - 1 computed from (free
+    // Direct pipeline over a ring of NS stages, slab j in stage j % NS (at least NS - 1 slabs). Step k issues the loads of slab k + NS - 1 into the stage that step k - 1 computed from (free
     // since the barrier that ended step k - 1), computes slab k, then waits until its own loads of slab
     // k + 1 have landed (the younger ones stay in flight) and meets the other wavefronts at the barrier.
     constexpr int LPS = A_LOADS + B_LOADS;   // loads per slab and loading wavefront
@@ -392,6 +391,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
       for (int k0 = 0; k0 < nk; k0 += NS) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
+          if (k0 + s >= nk) break;                  // uniform (slab counts that are no multiple of NS)
           const bool more = k0 + s + NS - 1 < nk;   // uniform
           if (more) load_direct(k0 + s + NS - 1, (s + NS - 1) % NS);
           if (more) wait_loads_and_lds<(NS - 2) * LPS>();
@@ -403,6 +403,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
       for (int k0 = 0; k0 < nk; k0 += NS) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
+          if (k0 + s >= nk) break;                  // uniform
           const bool more = k0 + s + NS - 1 < nk;   // uniform
           if (!PW && more) load_direct(k0 + s + NS - 1, (s + NS - 1) % NS);
           compute(s);
