@@ -2,6 +2,7 @@
 // reductions and the Philox4x32-10 dropout draw.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 namespace slapo {
@@ -70,10 +71,22 @@ __device__ __forceinline__ float to_f32(float f) { return f; }
 __device__ __forceinline__ void from_f32(bf16_t& d, float f) { d = f32_to_bf16(f); }
 __device__ __forceinline__ void from_f32(float& d, float f) { d = f; }
 
+// Sum over the 64 lanes, returned to every lane. Data-parallel-primitive moves (quad permutes, mirrors inside
+// rows of 16 lanes, then the row broadcasts) keep the whole reduction in the vector ALU: six dependent adds
+// and one lane read instead of six round trips through the LDS crossbar.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  auto dpp = [](float x, auto ctrl, auto row_mask) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                                                   decltype(row_mask)::value, 0xf, true));
+  };
+  using std::integral_constant;
+  v += dpp(v, integral_constant<int, 0xb1>{}, integral_constant<int, 0xf>{});    // quad_perm [1,0,3,2]
+  v += dpp(v, integral_constant<int, 0x4e>{}, integral_constant<int, 0xf>{});    // quad_perm [2,3,0,1]
+  v += dpp(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xf>{});   // row_half_mirror
+  v += dpp(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xf>{});   // row_mirror: every lane holds its row's sum
+  v += dpp(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{});   // row_bcast15 into rows 1 and 3
+  v += dpp(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{});   // row_bcast31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
