@@ -452,8 +452,28 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   const int n = n0 + wn0 + cc * 8;
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if ((EPI == EPI_BIAS || EPI == EPI_BIAS_ACT) && n < N) load8(bias + n, bv);
+  // The auxiliary input of a 32-row slab is fetched one slab ahead (clamped addresses, so the loads are
+  // unconditional): its latency passes while the slab before it is staged and written out.
+  constexpr bool AUX = (EPI == EPI_DACT || EPI == EPI_ADD);
+  constexpr int NP = 32 / RPP;
+  u32x4_t au[TM][NP];
+  auto aux_fetch = [&](int i, u32x4_t (&dst)[NP]) {
+    const int nc = n < N ? n : N - 8;
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass) {
+      int m = m0 + wm0 + i * 32 + pass * RPP + rr;
+      m = m < M ? m : M - 1;
+      dst[pass] = *reinterpret_cast<const u32x4_t*>(aux_in + (int64_t)m * N + nc);
+    }
+  };
+  auto aux_get = [](const u32x4_t& w, float (&u)[8]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { u[2 * e] = bf16lo_to_f32(w[e]); u[2 * e + 1] = bf16hi_to_f32(w[e]); }
+  };
+  if (AUX) aux_fetch(0, au[0]);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    if (AUX && i + 1 < TM) aux_fetch(i + 1, au[i + 1]);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -488,7 +508,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
           }
         } else if (EPI == EPI_DACT) {
           float u[8];
-          load8(aux_in + idx, u);
+          aux_get(au[i][pass], u);
           if (act == ACT_RELU) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = u[e] > 0.f ? v[e] : 0.f;
@@ -498,7 +518,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
           }
         } else if (EPI == EPI_ADD) {
           float u[8];
-          load8(aux_in + idx, u);
+          aux_get(au[i][pass], u);
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += u[e];
         }
