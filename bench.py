@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--checkpoint", action="store_true",
+                    help="activation-checkpointing mode: nothing saved, backward recomputes the forward")
     ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for the HBM byte counters)")
@@ -91,7 +93,7 @@ def main():
     stream = torch.cuda.current_stream()
     params = W.make_params(cfg)
     x, dy, seqlens = W.make_inputs(cfg)
-    layer = B.Layer(cfg, params)
+    layer = B.Layer(cfg, params, checkpoint=1 if args.checkpoint else 0)
     xd, dyd = layer.to_device(x), layer.to_device(dy)
     sld = None if seqlens is None else torch.from_numpy(seqlens).cuda()
     y = torch.empty_like(xd)
@@ -149,6 +151,10 @@ def main():
                 "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                 "avg_launch_us": dom_ms * 1e3, "flop_per_launch": dom_flops}
 
+    if args.checkpoint:   # the isolated-kernel figures below read saved activations: take them from a plain layer
+        layer = B.Layer(cfg, params)
+        B.slapo_layer_fwd(layer.desc, layer.params, xd, sld, y, layer.saved, layer.scratch)
+        torch.cuda.synchronize()
     # for reference: the largest forward GEMM with its fused bias+activation epilogue (FFN1)
     y1 = layer.saved_tensor("n2" if cfg.pre_ln else "y1")
     u = layer.saved_tensor("u")
@@ -197,7 +203,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": cfg.name, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                       "heads": cfg.heads, "ffn": cfg.ffn, "causal": cfg.causal, "dropout_p": cfg.dropout_p,
-                      "pre_ln": cfg.pre_ln, "parallelism": "single-gpu"},
+                      "pre_ln": cfg.pre_ln, "checkpoint": int(args.checkpoint), "parallelism": "single-gpu"},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, params, x, dy, seqlens)

@@ -65,6 +65,12 @@ typedef struct {
   int32_t layer_id;         /* mixed into the dropout counter so stacked layers differ         */
   float ln_eps;             /* LayerNorm epsilon (inside the square root)                      */
   int32_t accumulate_grads; /* 0: overwrite parameter gradients, 1: add to them                */
+  int32_t checkpoint;       /* 1: activation checkpointing (section 2.2: "the effective activation
+                               checkpointing"): forward keeps nothing, backward recomputes the
+                               forward from x first. No `saved` buffer exists (size 0, the argument is
+                               ignored and may be NULL); `scratch` is larger instead. The regenerated
+                               dropout masks make the recomputation exact: gradients are bit for bit
+                               those of checkpoint = 0.                                          */
 } slapo_layer_desc;
 
 /* Parameters: wqkv [3H,H] = [Wq;Wk;Wv] stacked on the output dim, bqkv [3H], wo [H,H], bo [H],
@@ -81,7 +87,8 @@ typedef struct {
 /* Sizes in bytes of the two caller-provided device buffers: `saved` carries activations from
  * slapo_layer_fwd to slapo_layer_bwd (QKV, attention output, logsumexp, pre-norm sums, LayerNorm
  * statistics, FFN pre-activation and activation) and must stay untouched in between; `scratch` is
- * free for reuse as soon as a call's work has completed on the stream. */
+ * free for reuse as soon as a call's work has completed on the stream (so one scratch buffer can serve
+ * every layer of a stack). With desc->checkpoint = 1, saved_bytes is 0. */
 int slapo_layer_workspace(const slapo_layer_desc *desc, size_t *saved_bytes, size_t *scratch_bytes);
 
 /* Named regions inside `saved`, for tests and tools. Writes byte offset and byte length; returns

@@ -21,7 +21,7 @@ class LayerDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32),
                 ("ffn", C.c_int32), ("causal", C.c_int32), ("dropout_p", C.c_float), ("seed", C.c_uint64),
                 ("dtype", C.c_int32), ("act", C.c_int32), ("pre_ln", C.c_int32), ("layer_id", C.c_int32),
-                ("ln_eps", C.c_float), ("accumulate_grads", C.c_int32)]
+                ("ln_eps", C.c_float), ("accumulate_grads", C.c_int32), ("checkpoint", C.c_int32)]
 
 
 class _Ptrs(C.Structure):
@@ -98,7 +98,7 @@ def _stream(stream=None):
 def make_desc(cfg=None, **kw) -> LayerDesc:
     """Builds a descriptor from a workloads.LayerConfig-like object and/or keyword overrides."""
     vals = dict(batch=1, seq=1, hidden=64, heads=1, ffn=64, causal=0, dropout_p=0.0, seed=0, dtype=BF16, act=GELU,
-                pre_ln=0, layer_id=0, ln_eps=1e-5, accumulate_grads=0)
+                pre_ln=0, layer_id=0, ln_eps=1e-5, accumulate_grads=0, checkpoint=0)
     if cfg is not None:
         for k in vals:
             if hasattr(cfg, k):
@@ -196,7 +196,7 @@ class Layer:
         self.params = {k: torch.from_numpy(v).to(self.device).to(self.dt).contiguous() for k, v in params_np.items()}
         self.grads = {k: torch.zeros_like(v) for k, v in self.params.items()}
         sb, wb = slapo_layer_workspace(self.desc)
-        self.saved = torch.empty(sb, dtype=torch.uint8, device=self.device)
+        self.saved = torch.empty(sb, dtype=torch.uint8, device=self.device) if sb else None   # None: checkpoint mode
         self.scratch = torch.empty(wb, dtype=torch.uint8, device=self.device)
 
     def to_device(self, a_np):

@@ -28,6 +28,7 @@ int check_desc(const slapo_layer_desc* d) {
   if (d->dtype != SLAPO_BF16 && d->dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
   if (d->act != SLAPO_GELU_ERF && d->act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
   if ((d->causal != 0 && d->causal != 1) || (d->pre_ln != 0 && d->pre_ln != 1)) return SLAPO_ERR_UNSUPPORTED;
+  if (d->checkpoint != 0 && d->checkpoint != 1) return SLAPO_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->seq * 3 * d->hidden >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->seq * d->ffn >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   return SLAPO_OK;
@@ -105,7 +106,7 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
 }
 
 struct ScratchLayout {
-  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, total;
+  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, acts, total;
 };
 ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
@@ -124,6 +125,9 @@ ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t widest = F > 3 * H ? F : 3 * H;
   L.part_col = take((size_t)colsum_blocks((int64_t)T) * widest * 4);
   L.part_col2 = take((size_t)colsum_blocks((int64_t)T) * widest * 4);   // the two streams of backward each own one
+  // checkpoint mode: the activations that forward would hand to backward live here instead, for the
+  // duration of one call only (backward recomputes them), so the caller keeps nothing per layer but x
+  L.acts = d->checkpoint ? take(saved_layout(d).total) : 0;
   L.total = o;
   return L;
 }
@@ -149,7 +153,7 @@ int slapo_layer_workspace(const slapo_layer_desc* desc, size_t* saved_bytes, siz
   if (!saved_bytes || !scratch_bytes) return SLAPO_ERR_NULL;
   const int rc = check_desc(desc);
   if (rc) return rc;
-  *saved_bytes = saved_layout(desc).total;
+  *saved_bytes = desc->checkpoint ? 0 : saved_layout(desc).total;
   *scratch_bytes = scratch_layout(desc).total;
   return SLAPO_OK;
 }
@@ -182,16 +186,10 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
   return SLAPO_OK;
 }
 
-int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
-                    void* y, void* saved, void* scratch, void* stream) {
-  int rc = check_desc(d);
-  if (rc) return rc;
-  if (!p || !x || !y || !saved || !scratch) return SLAPO_ERR_NULL;
-  const void* ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
-  for (const void* q : ps) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
-  if (misaligned(x) || misaligned(y) || misaligned(saved) || misaligned(scratch)) return SLAPO_ERR_ALIGN;
-
-  hipStream_t st = (hipStream_t)stream;
+// The forward launch sequence; `saved` receives the activations. Also the first half of a checkpointed
+// backward, which is why it is a function of its own.
+static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
+                        void* y, void* saved, void* scratch, hipStream_t st) {
   const int f32 = d->dtype == SLAPO_FP32;
   const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
   const SavedLayout L = saved_layout(d);
@@ -224,6 +222,18 @@ int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     void* z2 = sv + L.z2;
     launch_bdrln_fwd(f32, T, H, r, p->b2, y1, p->ln2_g, p->ln2_b, z2, y, mu2, rstd2, dp1, d->ln_eps, st);
   }
+}
+
+int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
+                    void* y, void* saved, void* scratch, void* stream) {
+  int rc = check_desc(d);
+  if (rc) return rc;
+  if (!p || !x || !y || !scratch || (!saved && !d->checkpoint)) return SLAPO_ERR_NULL;
+  const void* ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
+  for (const void* q : ps) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
+  if (misaligned(x) || misaligned(y) || misaligned(scratch) || (!d->checkpoint && misaligned(saved))) return SLAPO_ERR_ALIGN;
+  if (d->checkpoint) saved = (char*)scratch + scratch_layout(d).acts;   // transient: nothing is kept for backward
+  run_forward(d, p, x, seqlens, y, saved, scratch, (hipStream_t)stream);
   return finish();
 }
 
@@ -232,18 +242,27 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
                     void* stream) {
   int rc = check_desc(d);
   if (rc) return rc;
-  if (!p || !x || !dy || !saved || !dx || !gr || !scratch) return SLAPO_ERR_NULL;
+  if (!p || !x || !dy || !dx || !gr || !scratch || (!saved && !d->checkpoint)) return SLAPO_ERR_NULL;
   const void* ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
   const void* gs[12] = {gr->wqkv, gr->bqkv, gr->wo, gr->bo, gr->ln1_g, gr->ln1_b, gr->w1, gr->b1, gr->w2, gr->b2, gr->ln2_g, gr->ln2_b};
   for (const void* q : ps) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
   for (const void* q : gs) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
-  if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(saved) || misaligned(scratch)) return SLAPO_ERR_ALIGN;
+  if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(scratch) || (!d->checkpoint && misaligned(saved))) return SLAPO_ERR_ALIGN;
 
   hipStream_t st = (hipStream_t)stream;
   const int f32 = d->dtype == SLAPO_FP32, acc = d->accumulate_grads ? 1 : 0;
   const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
   const SavedLayout L = saved_layout(d);
   const ScratchLayout W = scratch_layout(d);
+  if (d->checkpoint) {
+    // Activation checkpointing (section 2.2, the paper's third optimisation): nothing but x was kept, so run
+    // the forward again into the transient region. The dropout masks are a pure function of (seed, layer,
+    // site, element), so the recomputed activations are bit for bit those of the original forward. The layer
+    // output lands in a gradient buffer that backward overwrites later.
+    char* acts = (char*)scratch + W.acts;
+    run_forward(d, p, x, seqlens, (char*)scratch + W.t1, acts, scratch, st);
+    saved = acts;
+  }
   const char* sv = (const char*)saved;
   char* sc = (char*)scratch;
   const void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *u = sv + L.u, *g = sv + L.g;

@@ -26,8 +26,10 @@ def test_descriptor_validation():
     ok = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024)
     saved, scratch = B.slapo_layer_workspace(ok)
     assert saved > 0 and scratch > 0
+    ck_saved, ck_scratch = B.slapo_layer_workspace(B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024, checkpoint=1))
+    assert ck_saved == 0 and scratch + saved <= ck_scratch <= scratch + saved + 256   # the activations move into scratch
     bad = [
-        (dict(heads=5), -2), (dict(batch=0), -2), (dict(dropout_p=1.0), -2), (dict(dropout_p=-0.1), -2),
+        (dict(checkpoint=2), -3), (dict(heads=5), -2), (dict(batch=0), -2), (dict(dropout_p=1.0), -2), (dict(dropout_p=-0.1), -2),
         (dict(hidden=256, heads=8), -3), (dict(hidden=8192, heads=64), -3), (dict(dtype=7), -3), (dict(act=3), -3),
         (dict(ffn=1001), -4), (dict(ln_eps=0.0), -2),
     ]
@@ -45,6 +47,9 @@ def test_null_and_alignment_errors_come_before_any_device_work():
     params = B._Ptrs(**{n: 4096 for n in B.PARAM_NAMES})
     assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), None, None, 4096, 4096, 4096, None) == -1
     assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), 4096 + 4, None, 4096, 4096, 4096, None) == -4
+    ck = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024, checkpoint=1)
+    assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), 4096, None, 4096, None, 4096, None) == -1    # saved is required ...
+    assert lib.slapo_layer_fwd(C.byref(ck), C.byref(params), 4096 + 4, None, 4096, None, 4096, None) == -4  # ... but not when checkpointing
     params.wo = None
     assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), 4096, None, 4096, 4096, 4096, None) == -1
     assert lib.slapo_gemm(0, 0, 0, 0, 128, 128, 0, 4096, 4096, 4096, None, None, None, None) == -2

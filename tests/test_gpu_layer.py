@@ -97,6 +97,26 @@ def test_zero_dropout_matches_layer_without_dropout_bitwise():
     assert torch.equal(y, y2)
 
 
+@pytest.mark.parametrize("idx", [0, 2, 4])
+def test_checkpoint_mode_recomputes_to_the_same_bits(idx):
+    """Activation checkpointing: no saved buffer, backward recomputes the forward; everything bit-identical."""
+    cfg = SMALL[idx]
+    errs, layer, (xd, sld, dyd, y, dx) = run_case(cfg, check_saved=False)
+    g1 = {k: v.clone() for k, v in layer.grads.items()}
+    params = W.make_params(cfg, perturbed=True)
+    ck = B.Layer(cfg, params, checkpoint=1)
+    assert ck.saved is None and ck.scratch.numel() > layer.scratch.numel()
+    y2 = ck.forward(xd, sld)
+    ck.scratch.fill_(0xAB)                       # nothing may survive from forward to backward
+    dx2 = ck.backward(xd, sld, dyd)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(dx, dx2)
+    for k in W.PARAM_NAMES:
+        assert torch.equal(g1[k], ck.grads[k]), k
+    tol = TOL[cfg.dtype]                         # and therefore the same parity with the oracle
+    assert all(v <= tol for v in errs.values()), errs
+
+
 @pytest.mark.parametrize("key", ["C2", "C3", "C4"])
 def test_layer_parity_full_size(key):
     """The benchmark shapes themselves, in the launch configuration bench.py times."""
