@@ -73,7 +73,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="C5 = the 24-layer stack (one step = 24 layer forwards, then 24 layer backwards)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--checkpoint", action="store_true",
                     help="activation-checkpointing mode: nothing saved, backward recomputes the forward")
@@ -103,6 +104,15 @@ def main():
         B.slapo_layer_fwd(layer.desc, layer.params, xd, sld, y, layer.saved, layer.scratch)
         B.slapo_layer_bwd(layer.desc, layer.params, xd, sld, dyd, layer.saved, dx, layer.grads, layer.scratch)
 
+    if cfg.n_layers > 1:   # the stack: per-layer weights seeded by the layer index, dy injected at the top
+        stack = B.Stack(cfg, [W.make_params(cfg, layer_id=l) for l in range(cfg.n_layers)],
+                        checkpoint=1 if args.checkpoint else 0)
+
+        def step():
+            B.slapo_stack_fwd(stack.desc, stack.params, xd, sld, y, stack.acts, stack.saved, stack.scratch)
+            B.slapo_stack_bwd(stack.desc, stack.params, xd, sld, dyd, stack.acts, stack.saved, dx, stack.grads,
+                              stack.scratch)
+
     if args.calibrate_copy:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -124,6 +134,7 @@ def main():
     ms = max(wall_ms, gpu_ms)
 
     total_flops, gemm_fwd, att_fwd = layer_flops(cfg, seqlens)
+    total_flops *= cfg.n_layers
     T, H, F = cfg.tokens, cfg.hidden, cfg.ffn
     dt, act = cfg.dtype, cfg.act
 
@@ -153,6 +164,7 @@ def main():
 
     if args.checkpoint:   # the isolated-kernel figures below read saved activations: take them from a plain layer
         layer = B.Layer(cfg, params)
+    if args.checkpoint or cfg.n_layers > 1:
         B.slapo_layer_fwd(layer.desc, layer.params, xd, sld, y, layer.saved, layer.scratch)
         torch.cuda.synchronize()
     # for reference: the largest forward GEMM with its fused bias+activation epilogue (FFN1)
@@ -203,7 +215,8 @@ def main():
            "data": "synthetic",
            "config": {"workload": cfg.name, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                       "heads": cfg.heads, "ffn": cfg.ffn, "causal": cfg.causal, "dropout_p": cfg.dropout_p,
-                      "pre_ln": cfg.pre_ln, "checkpoint": int(args.checkpoint), "parallelism": "single-gpu"},
+                      "pre_ln": cfg.pre_ln, "layers": cfg.n_layers, "checkpoint": int(args.checkpoint),
+                      "parallelism": "single-gpu"},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, params, x, dy, seqlens)

@@ -114,6 +114,24 @@ int slapo_layer_bwd(const slapo_layer_desc *desc, const slapo_layer_params *para
                     const int32_t *seqlens, const void *dy, const void *saved, void *dx,
                     const slapo_layer_grads *grads, void *scratch, void *stream);
 
+/* A stack of n_layers layers of one shape (the evaluation's encoder stacks, section 5): layer l runs with
+ * layer_id = desc->layer_id + l (so its dropout masks differ), parameters params[l] and gradients grads[l]
+ * (host arrays of n_layers pointer tables). Forward feeds x through the layers into y; backward takes
+ * dy = dL/dy at the top and produces every layer's parameter gradients and dx = dL/dx at the bottom.
+ *   acts:    device, (n_layers-1) x [B,S,H]: the outputs of layers 0..n_layers-2, kept from forward to backward
+ *            (may be NULL for one layer)
+ *   saved:   device, n_layers x the `saved` buffer of one layer (size 0 / ignored with desc->checkpoint: then
+ *            acts and x are all that survives the forward pass)
+ *   scratch: device, one layer's scratch plus two [B,S,H] gradient buffers; free between calls
+ * Sizes come from slapo_stack_workspace. Errors as for the layer calls; n_layers <= 0 is SLAPO_ERR_SHAPE. */
+int slapo_stack_workspace(const slapo_layer_desc *desc, int32_t n_layers, size_t *acts_bytes, size_t *saved_bytes,
+                          size_t *scratch_bytes);
+int slapo_stack_fwd(const slapo_layer_desc *desc, int32_t n_layers, const slapo_layer_params *params, const void *x,
+                    const int32_t *seqlens, void *y, void *acts, void *saved, void *scratch, void *stream);
+int slapo_stack_bwd(const slapo_layer_desc *desc, int32_t n_layers, const slapo_layer_params *params, const void *x,
+                    const int32_t *seqlens, const void *dy, const void *acts, const void *saved, void *dx,
+                    const slapo_layer_grads *grads, void *scratch, void *stream);
+
 const char *slapo_status_string(int status);
 
 /* ---- building blocks, exported for per-kernel tests and measurement ---------------------------- */

@@ -53,6 +53,9 @@ def lib():
             "slapo_layer_saved_region": [dp, C.c_char_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)],
             "slapo_layer_fwd": [dp, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, vp],
             "slapo_layer_bwd": [dp, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, C.POINTER(_Ptrs), vp, vp],
+            "slapo_stack_workspace": [dp, i32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)],
+            "slapo_stack_fwd": [dp, i32, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, vp, vp],
+            "slapo_stack_bwd": [dp, i32, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, vp, C.POINTER(_Ptrs), vp, vp],
             "slapo_gemm": [i32, i32, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp],
             "slapo_attn_fwd": [dp, vp, vp, vp, vp, vp],
             "slapo_attn_bwd": [dp, vp, vp, vp, vp, vp, vp, vp, vp],
@@ -184,6 +187,58 @@ def slapo_colreduce_partials(dtype, nblk, stride, N, partials, out, accumulate=0
 
 def slapo_dropout_mask(desc, site, T, mask, stream=None):
     _check(lib().slapo_dropout_mask(C.byref(desc), site, T, _p(mask), _stream(stream)), "slapo_dropout_mask")
+
+
+def slapo_stack_workspace(desc: LayerDesc, n_layers: int):
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check(lib().slapo_stack_workspace(C.byref(desc), n_layers, C.byref(a), C.byref(b), C.byref(c)),
+           "slapo_stack_workspace")
+    return a.value, b.value, c.value
+
+
+def _ptr_tables(layers: list):
+    arr = (_Ptrs * len(layers))()
+    for i, t in enumerate(layers):
+        arr[i] = _ptr_table(t)
+    return arr
+
+
+def slapo_stack_fwd(desc, params: list, x, seqlens, y, acts, saved, scratch, stream=None):
+    _check(lib().slapo_stack_fwd(C.byref(desc), len(params), _ptr_tables(params), _p(x), _p(seqlens), _p(y), _p(acts),
+                                 _p(saved), _p(scratch), _stream(stream)), "slapo_stack_fwd")
+
+
+def slapo_stack_bwd(desc, params: list, x, seqlens, dy, acts, saved, dx, grads: list, scratch, stream=None):
+    _check(lib().slapo_stack_bwd(C.byref(desc), len(params), _ptr_tables(params), _p(x), _p(seqlens), _p(dy), _p(acts),
+                                 _p(saved), _p(dx), _ptr_tables(grads), _p(scratch), _stream(stream)), "slapo_stack_bwd")
+
+
+class Stack:
+    """Convenience holder for a stack of layers of one shape: per-layer parameters and gradients, shared workspaces."""
+
+    def __init__(self, cfg, params_np: list, device="cuda:0", **desc_kw):
+        self.desc = make_desc(cfg, **desc_kw)
+        self.device = torch.device(device)
+        self.dt = torch_dtype(self.desc)
+        self.params = [{k: torch.from_numpy(v).to(self.device).to(self.dt).contiguous() for k, v in p.items()}
+                       for p in params_np]
+        self.grads = [{k: torch.zeros_like(v) for k, v in p.items()} for p in self.params]
+        ab, sb, wb = slapo_stack_workspace(self.desc, len(self.params))
+        mk = lambda n: torch.empty(n, dtype=torch.uint8, device=self.device) if n else None
+        self.acts, self.saved, self.scratch = mk(ab), mk(sb), mk(wb)
+
+    def to_device(self, a_np):
+        return torch.from_numpy(a_np).to(self.device).to(self.dt).contiguous()
+
+    def forward(self, x, seqlens=None):
+        y = torch.empty_like(x)
+        slapo_stack_fwd(self.desc, self.params, x, seqlens, y, self.acts, self.saved, self.scratch)
+        return y
+
+    def backward(self, x, seqlens, dy):
+        dx = torch.empty_like(x)
+        slapo_stack_bwd(self.desc, self.params, x, seqlens, dy, self.acts, self.saved, dx, self.grads, self.scratch)
+        return dx
 
 
 class Layer:

@@ -341,6 +341,65 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   return finish();
 }
 
+// ---- a stack of layers of one shape ------------------------------------------------------------------
+static size_t stack_act_bytes(const slapo_layer_desc* d) {
+  return (size_t)d->batch * d->seq * d->hidden * (d->dtype == SLAPO_FP32 ? 4 : 2);
+}
+
+int slapo_stack_workspace(const slapo_layer_desc* desc, int32_t n_layers, size_t* acts_bytes, size_t* saved_bytes,
+                          size_t* scratch_bytes) {
+  if (!acts_bytes || !saved_bytes || !scratch_bytes) return SLAPO_ERR_NULL;
+  const int rc = check_desc(desc);
+  if (rc) return rc;
+  if (n_layers <= 0) return SLAPO_ERR_SHAPE;
+  *acts_bytes = (size_t)(n_layers - 1) * stack_act_bytes(desc);
+  *saved_bytes = desc->checkpoint ? 0 : (size_t)n_layers * saved_layout(desc).total;
+  *scratch_bytes = scratch_layout(desc).total + 2 * align256(stack_act_bytes(desc));
+  return SLAPO_OK;
+}
+
+int slapo_stack_fwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_layer_params* params, const void* x,
+                    const int32_t* seqlens, void* y, void* acts, void* saved, void* scratch, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (n_layers <= 0) return SLAPO_ERR_SHAPE;
+  if (!params || !x || !y || !scratch || (n_layers > 1 && !acts) || (!saved && !desc->checkpoint)) return SLAPO_ERR_NULL;
+  const size_t ab = stack_act_bytes(desc), sb = desc->checkpoint ? 0 : saved_layout(desc).total;
+  slapo_layer_desc d = *desc;
+  for (int l = 0; l < n_layers; ++l) {
+    d.layer_id = desc->layer_id + l;
+    const void* in = l == 0 ? x : (const char*)acts + (size_t)(l - 1) * ab;
+    void* out = l == n_layers - 1 ? y : (char*)acts + (size_t)l * ab;
+    rc = slapo_layer_fwd(&d, params + l, in, seqlens, out, saved ? (char*)saved + (size_t)l * sb : nullptr, scratch, stream);
+    if (rc) return rc;
+  }
+  return SLAPO_OK;
+}
+
+int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_layer_params* params, const void* x,
+                    const int32_t* seqlens, const void* dy, const void* acts, const void* saved, void* dx,
+                    const slapo_layer_grads* grads, void* scratch, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (n_layers <= 0) return SLAPO_ERR_SHAPE;
+  if (!params || !grads || !x || !dy || !dx || !scratch || (n_layers > 1 && !acts) || (!saved && !desc->checkpoint))
+    return SLAPO_ERR_NULL;
+  const size_t ab = stack_act_bytes(desc), sb = desc->checkpoint ? 0 : saved_layout(desc).total;
+  char* pong = (char*)scratch + scratch_layout(desc).total;   // two gradient buffers behind the layer's own scratch
+  slapo_layer_desc d = *desc;
+  const void* gin = dy;
+  for (int l = n_layers - 1; l >= 0; --l) {
+    d.layer_id = desc->layer_id + l;
+    const void* in = l == 0 ? x : (const char*)acts + (size_t)(l - 1) * ab;
+    void* gout = l == 0 ? dx : pong + (size_t)(l & 1) * align256(ab);
+    rc = slapo_layer_bwd(&d, params + l, in, seqlens, gin, saved ? (const char*)saved + (size_t)l * sb : nullptr, gout,
+                         grads + l, scratch, stream);
+    if (rc) return rc;
+    gin = gout;
+  }
+  return SLAPO_OK;
+}
+
 int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
                const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
   if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;

@@ -72,3 +72,22 @@ def test_saved_regions_are_disjoint_and_inside_the_buffer():
         assert spans[-1][0] + spans[-1][1] <= saved
         with pytest.raises(B.SlapoError):
             B.slapo_layer_saved_region(d, "y1" if pre_ln else "n1")
+
+
+def test_stack_workspace_and_argument_checks():
+    d = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024)
+    saved, scratch = B.slapo_layer_workspace(d)
+    acts, ssaved, sscratch = B.slapo_stack_workspace(d, 24)
+    act = 2 * 128 * 256 * 2
+    assert acts == 23 * act and ssaved == 24 * saved and scratch + 2 * act <= sscratch <= scratch + 2 * act + 512
+    assert B.slapo_stack_workspace(d, 1)[0] == 0
+    with pytest.raises(B.SlapoError) as e:
+        B.slapo_stack_workspace(d, 0)
+    assert e.value.status == -2
+    ck = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024, checkpoint=1)
+    assert B.slapo_stack_workspace(ck, 24)[1] == 0
+    lib = B.lib()
+    tabs = (B._Ptrs * 2)()
+    assert lib.slapo_stack_fwd(C.byref(d), 2, tabs, 4096, None, 4096, None, 4096, 4096, None) == -1   # acts missing
+    assert lib.slapo_stack_fwd(C.byref(d), 2, tabs, 4096, None, 4096, 4096, 4096, 4096, None) == -1   # NULL parameters
+    assert lib.slapo_stack_bwd(C.byref(d), 0, tabs, 4096, None, 4096, 4096, 4096, 4096, tabs, 4096, None) == -2

@@ -1,0 +1,136 @@
+"""GPU parity of a stack of layers (slapo_stack_fwd / slapo_stack_bwd) vs the fp64 oracle run layer after layer.
+
+The evaluation's 24-layer stack is 24 times the same kernels; what the stack adds is the chaining (layer l's
+output is layer l+1's input, gradients flow back through two alternating buffers) and the per-layer dropout
+streams (layer_id = first + l). Checked here on three layers: end to end against the oracle chain, bit for bit
+against the same layers called one by one, and bit for bit with activation checkpointing on.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import layer as L
+from paper_2302_08005_amd import binding as B
+from gpu_util import DEV, TOL, err
+
+pytestmark = pytest.mark.gpu
+
+N_LAYERS = 3
+STACKS = [
+    W.LayerConfig("stack-postln-bf16", 2, 192, 256, 4, 1024, causal=0, dropout_p=0.1, dtype=W.BF16, act=W.GELU,
+                  len_lo=100, len_hi=192, config_id=21),
+    W.LayerConfig("stack-preln-causal-bf16", 2, 128, 256, 2, 768, causal=1, dropout_p=0.1, dtype=W.BF16, act=W.GELU,
+                  pre_ln=1, config_id=22),
+    W.LayerConfig("stack-postln-fp32", 1, 96, 128, 2, 512, causal=0, dropout_p=0.2, dtype=W.FP32, act=W.GELU,
+                  config_id=23),
+]
+
+
+def oracle_chain(cfg, params, x, sl, dy):
+    caches, h = [], x.astype(np.float64)
+    for l in range(N_LAYERS):
+        c = L.layer_forward(cfg.replace(layer_id=l), params[l], h, sl)
+        caches.append(c)
+        h = c["y"]
+    grads, g = [None] * N_LAYERS, dy.astype(np.float64)
+    for l in reversed(range(N_LAYERS)):
+        grads[l] = L.layer_backward(cfg.replace(layer_id=l), params[l], caches[l], g)
+        g = grads[l]["dx"]
+    return h, g, grads
+
+
+@pytest.mark.parametrize("cfg", STACKS, ids=lambda c: c.name)
+def test_stack_matches_oracle_chain_and_single_layer_calls(cfg):
+    params = [W.make_params(cfg, layer_id=l, perturbed=True) for l in range(N_LAYERS)]
+    x, dy, sl = W.make_inputs(cfg)
+    y_ref, dx_ref, g_ref = oracle_chain(cfg, params, x, sl, dy)
+
+    st = B.Stack(cfg, params)
+    xd, dyd = st.to_device(x), st.to_device(dy)
+    sld = None if sl is None else torch.from_numpy(sl).to(DEV)
+    y = st.forward(xd, sld)
+    dx = st.backward(xd, sld, dyd)
+    torch.cuda.synchronize()
+    tol = TOL[cfg.dtype]
+    errs = {"y": err(y, y_ref), "dx": err(dx, dx_ref)}
+    for l in range(N_LAYERS):
+        for k in W.PARAM_NAMES:
+            errs[f"L{l}.d{k}"] = err(st.grads[l][k], g_ref[l][k])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
+
+    # the same layers one call at a time: identical kernels on identical inputs, so identical bits
+    layers = [B.Layer(cfg, params[l], layer_id=l) for l in range(N_LAYERS)]
+    hs = [xd]
+    for lay in layers:
+        hs.append(lay.forward(hs[-1], sld))
+    assert torch.equal(hs[-1], y)
+    g = dyd
+    for l in reversed(range(N_LAYERS)):
+        g = layers[l].backward(hs[l], sld, g)
+        for k in W.PARAM_NAMES:
+            assert torch.equal(layers[l].grads[k], st.grads[l][k]), (l, k)
+    assert torch.equal(g, dx)
+
+    # per-layer dropout streams: with dropout on, two layers of a stack must not share a mask
+    if cfg.dropout_p > 0:
+        same_id = [B.Layer(cfg, params[1], layer_id=0), B.Layer(cfg, params[1], layer_id=1)]
+        outs = [lay.forward(hs[1], sld) for lay in same_id]
+        assert not torch.equal(outs[0], outs[1]) and torch.equal(outs[1], hs[2])
+
+    # activation checkpointing through the stack: nothing saved, same bits
+    ck = B.Stack(cfg, params, checkpoint=1)
+    assert ck.saved is None
+    y2 = ck.forward(xd, sld)
+    ck.scratch.fill_(0x5A)
+    dx2 = ck.backward(xd, sld, dyd)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(dx, dx2)
+    for l in range(N_LAYERS):
+        for k in W.PARAM_NAMES:
+            assert torch.equal(ck.grads[l][k], st.grads[l][k]), (l, k)
+
+
+def test_one_layer_stack_is_the_layer():
+    cfg = STACKS[0]
+    params = [W.make_params(cfg, layer_id=0, perturbed=True)]
+    x, dy, sl = W.make_inputs(cfg)
+    st = B.Stack(cfg, params)
+    assert st.acts is None
+    lay = B.Layer(cfg, params[0])
+    xd, dyd = st.to_device(x), st.to_device(dy)
+    sld = torch.from_numpy(sl).to(DEV)
+    assert torch.equal(st.forward(xd, sld), lay.forward(xd, sld))
+    assert torch.equal(st.backward(xd, sld, dyd), lay.backward(xd, sld, dyd))
+
+
+def test_drift_over_24_bf16_layers_stays_small():
+    """End-to-end error of a 24-layer bf16 stack against the fp64 oracle chain (reported, bounded loosely).
+
+    Each layer on its own meets the 2e-2 bar (the layer tests, and the stack above, feed every layer inputs
+    both sides agree on). Run end to end, the storage roundings of 24 layers add up: measured 2.8e-2 on y,
+    2.7e-2 on dx, 2.3e-2 on the worst weight gradient for this configuration.
+    """
+    n = 24
+    cfg = W.LayerConfig("drift-24", 2, 128, 256, 4, 1024, causal=0, dropout_p=0.1, dtype=W.BF16, act=W.GELU,
+                        len_lo=64, len_hi=128, config_id=31)
+    params = [W.make_params(cfg, layer_id=l, perturbed=True) for l in range(n)]
+    x, dy, sl = W.make_inputs(cfg)
+    caches, h = [], x.astype(np.float64)
+    for l in range(n):
+        caches.append(L.layer_forward(cfg.replace(layer_id=l), params[l], h, sl))
+        h = caches[-1]["y"]
+    g, worst = dy.astype(np.float64), 0.0
+    st = B.Stack(cfg, params)
+    xd, dyd, sld = st.to_device(x), st.to_device(dy), torch.from_numpy(sl).to(DEV)
+    y = st.forward(xd, sld)
+    dx = st.backward(xd, sld, dyd)
+    torch.cuda.synchronize()
+    for l in reversed(range(n)):
+        gr = L.layer_backward(cfg.replace(layer_id=l), params[l], caches[l], g)
+        worst = max([worst] + [err(st.grads[l][k], gr[k]) for k in W.PARAM_NAMES])
+        g = gr["dx"]
+    drift = {"y": err(y, h), "dx": err(dx, g), "worst_grad": worst}
+    print("24-layer drift:", drift)
+    assert all(v <= 5e-2 for v in drift.values()), drift
