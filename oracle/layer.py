@@ -8,7 +8,9 @@ concatenated Q, K, V (section 2.2, step 1), softmax(Q K^T / sqrt(d)) V attention
 the output projection whose bias is moved into the following fused pattern, F.gelu(bias + x) in the
 feed-forward block and LayerNorm(dropout(bias + x) + residual) after both blocks (appendix schedule).
 The paper gives no equations; each op is the textbook one. Readings taken where the paper is silent:
-score scale 1/sqrt(head dim); no dropout on attention probabilities; exact erf GeLU; biased
+score scale 1/sqrt(head dim); dropout on the attention probabilities (the dropout(softmax(attn), p) of
+the listing in section 2.2 step 2) only when cfg.attn_dropout_p > 0, with its own mask stream (site 2, element
+index ((b*heads + a)*S + i)*S + j); exact erf GeLU; biased
 variance and eps inside the square root for LayerNorm; key-padding mask hides keys j >= len_b from
 every query row; [Wq; Wk; Wv] stacked on the output dimension; pre-LN layers normalise the block
 inputs and have no LayerNorm after the second residual.
@@ -65,10 +67,19 @@ def score_mask(cfg, seqlens, b):
     return ok
 
 
+def attention_keep(cfg):
+    """[B,h,S,S] array of 0/1 keep decisions for the attention probabilities (dropout site 2), or None."""
+    if not cfg.attn_dropout_p > 0:
+        return None
+    B, S, h = cfg.batch, cfg.seq, cfg.heads
+    return philox.keep_mask(B * h * S * S, cfg.attn_dropout_p, cfg.seed, 2, cfg.layer_id).reshape(B, h, S, S).astype(np.float64)
+
+
 def attention_fwd(cfg, qkv, seqlens):
-    """qkv [T,3H] -> (A [T,H], P [B,h,S,S], LSE [B,h,S])."""
+    """qkv [T,3H] -> (A [T,H], P [B,h,S,S], LSE [B,h,S]). P is the softmax before dropout; A uses the dropped P."""
     B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
     d = H // h
+    keep = attention_keep(cfg)
     A = np.zeros((B * S, H))
     P = np.zeros((B, h, S, S))
     LSE = np.zeros((B, h, S))
@@ -87,6 +98,8 @@ def attention_fwd(cfg, qkv, seqlens):
             p = ex / den
             P[b, a] = p
             LSE[b, a] = (m + np.log(den))[:, 0]
+            if keep is not None:
+                p = p * keep[b, a] / (1.0 - cfg.attn_dropout_p)
             A[rows, a * d:(a + 1) * d] = p @ v
     return A, P, LSE
 
@@ -96,6 +109,7 @@ def attention_bwd(cfg, qkv, P, dA):
     B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
     d = H // h
     dqkv = np.zeros_like(qkv)
+    keep = attention_keep(cfg)
     for b in range(B):
         rows = slice(b * S, (b + 1) * S)
         for a in range(h):
@@ -104,8 +118,13 @@ def attention_bwd(cfg, qkv, P, dA):
             v = qkv[rows, 2 * H + a * d:2 * H + (a + 1) * d]
             p = P[b, a]
             da = dA[rows, a * d:(a + 1) * d]
-            dv = p.T @ da
-            dp = da @ v.T
+            if keep is None:
+                dv = p.T @ da
+                dp = da @ v.T
+            else:                               # A = (P * keep / (1 - pd)) V
+                w = keep[b, a] / (1.0 - cfg.attn_dropout_p)
+                dv = (p * w).T @ da
+                dp = (da @ v.T) * w
             dsc = p * (dp - (p * dp).sum(axis=-1, keepdims=True))
             dqkv[rows, a * d:(a + 1) * d] = (dsc @ k) / np.sqrt(d)
             dqkv[rows, H + a * d:H + (a + 1) * d] = (dsc.T @ q) / np.sqrt(d)

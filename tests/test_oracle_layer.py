@@ -13,6 +13,9 @@ from oracle import layer as L
 VARIANTS = [dict(pre_ln=pl, act=act, causal=ca, len_hi=lh, len_lo=(2 if lh else 0))
             for pl, act, ca, lh in [(0, W.GELU, 0, 0), (0, W.GELU, 0, 6), (1, W.RELU, 1, 0),
                                     (1, W.GELU, 1, 6), (0, W.RELU, 1, 0), (1, W.GELU, 0, 5)]]
+# with dropout on the attention probabilities (section 2.2 step 2 listing): padded encoder, causal pre-LN decoder
+VARIANTS += [dict(pre_ln=0, act=W.GELU, causal=0, len_hi=6, len_lo=3, attn_dropout_p=0.3, seq=8),
+             dict(pre_ln=1, act=W.GELU, causal=1, len_hi=0, len_lo=0, attn_dropout_p=0.4, seq=8)]
 
 
 def _setup(**kw):
@@ -56,7 +59,7 @@ def test_backward_matches_central_finite_differences(variant):
     assert worst < 1e-6
 
 
-def _torch_layer(cfg, tp, x, sl, M1, M2):
+def _torch_layer(cfg, tp, x, sl, M1, M2, MA=None):
     """The same layer built only from torch CPU fp64 library ops, the dropout masks entering as constants."""
     B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
     d = H // h
@@ -71,7 +74,12 @@ def _torch_layer(cfg, tp, x, sl, M1, M2):
     a_in = ln(x, "ln1") if cfg.pre_ln else x
     q, k, v = F.linear(a_in, tp["wqkv"], tp["bqkv"]).split(H, dim=-1)
     heads = lambda t: t.reshape(B, S, h, d).transpose(1, 2)
-    A = F.scaled_dot_product_attention(heads(q), heads(k), heads(v), attn_mask=ok)
+    if MA is None:
+        A = F.scaled_dot_product_attention(heads(q), heads(k), heads(v), attn_mask=ok)
+    else:   # dropout(softmax(scores), p) @ v with the keep decisions given
+        sc = (heads(q) @ heads(k).transpose(-1, -2)) / d ** 0.5
+        pr = torch.softmax(sc.masked_fill(~ok, float("-inf")), dim=-1)
+        A = (pr * MA / (1.0 - cfg.attn_dropout_p)) @ heads(v)
     A = A.transpose(1, 2).reshape(B, S, H)
     z1 = x + M1 * (F.linear(A, tp["wo"]) + tp["bo"]) * scale
     f_in = ln(z1, "ln2") if cfg.pre_ln else ln(z1, "ln1")
@@ -89,7 +97,9 @@ def test_matches_torch_fp64_library_ops_and_autograd(variant):
     tp = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in params.items()}
     tx = torch.tensor(x, dtype=torch.float64, requires_grad=True)
     shape = (cfg.batch, cfg.seq, cfg.hidden)
-    y = _torch_layer(cfg, tp, tx, sl, torch.tensor(c["M1"]).reshape(shape), torch.tensor(c["M2"]).reshape(shape))
+    MA = L.attention_keep(cfg)
+    y = _torch_layer(cfg, tp, tx, sl, torch.tensor(c["M1"]).reshape(shape), torch.tensor(c["M2"]).reshape(shape),
+                     None if MA is None else torch.tensor(MA))
     assert L.max_rel_err(c["y"], y.detach().numpy()) < 1e-12
     y.backward(torch.tensor(dy))
     assert L.max_rel_err(g["dx"], tx.grad.numpy()) < 1e-11
@@ -195,3 +205,31 @@ def test_zero_dropout_is_identity_and_masked_positions_are_dropped():
     assert dropped.any() and (~dropped).any()
     assert np.array_equal(c["Z1"][dropped], c["X"][dropped])
     assert np.allclose(c["Z1"][~dropped], (c["X"] + 2.0 * (c["R1"] + params["bo"]))[~dropped], rtol=0, atol=1e-13)
+
+
+def test_attention_dropout_mask_stream_and_effect():
+    """Site 2: element ((b*heads + a)*S + i)*S + j of the Philox stream; dropped probabilities leave A, kept ones
+    are scaled by 1/(1-p); p = 0 is the plain attention bit for bit."""
+    from test_oracle_philox import _keep_scalar
+    cfg, params, x, dy, sl = _setup(attn_dropout_p=0.3, seq=8, len_hi=7, len_lo=4)
+    cfg = cfg.replace(seed=0x0123456789ABCDEF, layer_id=3)
+    keep = L.attention_keep(cfg)
+    B, h, S = cfg.batch, cfg.heads, cfg.seq
+    assert keep.shape == (B, h, S, S) and set(np.unique(keep)) <= {0.0, 1.0}
+    for (b, a, i, j) in [(0, 0, 0, 0), (0, 0, 0, 7), (0, 1, 3, 5), (1, 0, 7, 7), (1, 1, 2, 1), (1, 1, 7, 6)]:
+        e = ((b * h + a) * S + i) * S + j
+        assert bool(keep[b, a, i, j]) == _keep_scalar(e, 0.3, cfg.seed, 2, cfg.layer_id), (b, a, i, j)
+    # a different stream from the two residual sites
+    assert not np.array_equal(keep.reshape(-1)[:B * S * cfg.hidden],
+                              L.dropout_keep(cfg, 0).reshape(-1)[:keep.size][:B * S * cfg.hidden])
+    # effect on A, written out by hand for one (sample, head, query row)
+    qkv = L.layer_forward(cfg, params, x, sl)["QKV"]
+    A, P, _ = L.attention_fwd(cfg, qkv, sl)
+    H, d = cfg.hidden, cfg.hidden // cfg.heads
+    b, a, i = 1, 1, 5
+    v = qkv[b * S:(b + 1) * S, 2 * H + a * d:2 * H + (a + 1) * d]
+    want = sum(P[b, a, i, j] * keep[b, a, i, j] / 0.7 * v[j] for j in range(S))
+    assert np.allclose(A[b * S + i, a * d:(a + 1) * d], want, rtol=1e-13, atol=1e-15)
+    assert np.allclose(P[b, a].sum(axis=-1), 1.0)          # P itself stays the undropped softmax
+    A0, _, _ = L.attention_fwd(cfg.replace(attn_dropout_p=0.0), qkv, sl)
+    assert np.array_equal(A0[b * S + i, a * d:(a + 1) * d], (P[b, a] @ v)[i])

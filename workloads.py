@@ -26,6 +26,7 @@ class LayerConfig:
     ffn: int
     causal: int = 0
     dropout_p: float = 0.1
+    attn_dropout_p: float = 0.0   # dropout on the attention probabilities (0 = off, the benchmark configurations)
     seed: int = 0
     dtype: int = BF16
     act: int = GELU
