@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--checkpoint", action="store_true",
                     help="activation-checkpointing mode: nothing saved, backward recomputes the forward")
+    ap.add_argument("--attn-dropout", type=float, default=0.0,
+                    help="also drop attention probabilities with this probability (0 = the benchmark configuration)")
     ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for the HBM byte counters)")
@@ -94,6 +96,8 @@ def main():
     stream = torch.cuda.current_stream()
     params = W.make_params(cfg)
     x, dy, seqlens = W.make_inputs(cfg)
+    if args.attn_dropout:
+        cfg = cfg.replace(attn_dropout_p=args.attn_dropout)
     layer = B.Layer(cfg, params, checkpoint=1 if args.checkpoint else 0)
     xd, dyd = layer.to_device(x), layer.to_device(dy)
     sld = None if seqlens is None else torch.from_numpy(seqlens).cuda()
@@ -215,7 +219,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": cfg.name, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                       "heads": cfg.heads, "ffn": cfg.ffn, "causal": cfg.causal, "dropout_p": cfg.dropout_p,
-                      "pre_ln": cfg.pre_ln, "layers": cfg.n_layers, "checkpoint": int(args.checkpoint),
+                      "attn_dropout_p": cfg.attn_dropout_p, "pre_ln": cfg.pre_ln, "layers": cfg.n_layers, "checkpoint": int(args.checkpoint),
                       "parallelism": "single-gpu"},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:

@@ -57,7 +57,7 @@ typedef struct {
   int32_t batch, seq, hidden, heads, ffn;
   int32_t causal;           /* 1: query i sees keys j <= i                                     */
   float dropout_p;          /* probability of dropping, in [0,1); applied at the two fused
-                               bias+dropout+residual sites, not on attention probabilities     */
+                               bias+dropout+residual sites (attention probabilities: see below) */
   uint64_t seed;            /* dropout seed (Philox key)                                       */
   int32_t dtype;            /* SLAPO_BF16 | SLAPO_FP32: activations, weights and gradients     */
   int32_t act;              /* SLAPO_GELU_ERF (0.5 u (1 + erf(u/sqrt 2))) | SLAPO_RELU         */
@@ -71,6 +71,10 @@ typedef struct {
                                ignored and may be NULL); `scratch` is larger instead. The regenerated
                                dropout masks make the recomputation exact: gradients are bit for bit
                                those of checkpoint = 0.                                          */
+  float attn_dropout_p;     /* dropout on the attention probabilities, in [0,1): the
+                               dropout(softmax(attn), p) of the attention listing in section 2.2 step 2,
+                               applied inside the fused attention kernels (mask stream: site 2, element
+                               ((b*heads + a)*seq + i)*seq + j; needs seq % 8 == 0). 0 = none.     */
 } slapo_layer_desc;
 
 /* Parameters: wqkv [3H,H] = [Wq;Wk;Wv] stacked on the output dim, bqkv [3H], wo [H,H], bo [H],

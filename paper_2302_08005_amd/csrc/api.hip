@@ -29,6 +29,8 @@ int check_desc(const slapo_layer_desc* d) {
   if (d->act != SLAPO_GELU_ERF && d->act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
   if ((d->causal != 0 && d->causal != 1) || (d->pre_ln != 0 && d->pre_ln != 1)) return SLAPO_ERR_UNSUPPORTED;
   if (d->checkpoint != 0 && d->checkpoint != 1) return SLAPO_ERR_UNSUPPORTED;
+  if (!(d->attn_dropout_p >= 0.f && d->attn_dropout_p < 1.f)) return SLAPO_ERR_SHAPE;
+  if (d->attn_dropout_p > 0.f && d->seq % 8 != 0) return SLAPO_ERR_ALIGN;   // a mask block of 8 keys stays inside one query row
   if ((int64_t)d->batch * d->seq * 3 * d->hidden >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->seq * d->ffn >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   return SLAPO_OK;
@@ -43,6 +45,17 @@ DropoutParams make_dropout(const slapo_layer_desc* d, int site) {
   dp.thr = (uint32_t)llround((double)d->dropout_p * 65536.0);
   dp.scale = 1.0f / (1.0f - d->dropout_p);
   return dp;
+}
+
+AttnShape make_attn_shape(const slapo_layer_desc* d) {
+  AttnShape as = {d->batch, d->seq, d->hidden, d->heads, d->causal};
+  as.drop.key0 = (uint32_t)(d->seed & 0xffffffffu);
+  as.drop.key1 = (uint32_t)(d->seed >> 32);
+  as.drop.site = 2u;
+  as.drop.layer = (uint32_t)d->layer_id;
+  as.drop.thr = (uint32_t)llround((double)d->attn_dropout_p * 65536.0);
+  as.drop.scale = 1.0f / (1.0f - d->attn_dropout_p);
+  return as;
 }
 
 int finish() { return hipGetLastError() == hipSuccess ? SLAPO_OK : SLAPO_ERR_HIP; }
@@ -200,7 +213,7 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   float *lse = (float*)(sv + L.lse), *mu1 = (float*)(sv + L.mu1), *rstd1 = (float*)(sv + L.rstd1);
   float *mu2 = (float*)(sv + L.mu2), *rstd2 = (float*)(sv + L.rstd2);
   void* r = sc + W.t0;
-  const AttnShape as = {d->batch, d->seq, H, d->heads, d->causal};
+  const AttnShape as = make_attn_shape(d);
   const DropoutParams dp0 = make_dropout(d, 0), dp1 = make_dropout(d, 1);
 
   const void* attn_in = x;
@@ -270,7 +283,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   const float *mu2 = (const float*)(sv + L.mu2), *rstd2 = (const float*)(sv + L.rstd2);
   void *t0 = sc + W.t0, *t1 = sc + W.t1, *t2 = sc + W.t2, *t3 = sc + W.t3, *du = sc + W.du, *dqkv = sc + W.dqkv;
   float *delta = (float*)(sc + W.delta), *prow = (float*)(sc + W.part_row), *pcol = (float*)(sc + W.part_col), *pcol2 = (float*)(sc + W.part_col2);
-  const AttnShape as = {d->batch, d->seq, H, d->heads, d->causal};
+  const AttnShape as = make_attn_shape(d);
   const DropoutParams dp0 = make_dropout(d, 0), dp1 = make_dropout(d, 1);
   const int nrow = bdrln_bwd_blocks(T), ncol = colsum_blocks(T);
   // `st` carries the data-gradient chain; `ws` the weight / bias gradients that hang off it
@@ -426,7 +439,7 @@ int slapo_attn_fwd(const slapo_layer_desc* d, const void* qkv, const int32_t* se
   if (rc) return rc;
   if (!qkv || !out || !lse) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(out)) return SLAPO_ERR_ALIGN;
-  const AttnShape as = {d->batch, d->seq, d->hidden, d->heads, d->causal};
+  const AttnShape as = make_attn_shape(d);
   launch_attn_fwd(d->dtype == SLAPO_FP32, as, qkv, seqlens, out, lse, (hipStream_t)stream);
   return finish();
 }
@@ -437,7 +450,7 @@ int slapo_attn_bwd(const slapo_layer_desc* d, const void* qkv, const int32_t* se
   if (rc) return rc;
   if (!qkv || !out || !dout || !lse || !delta || !dqkv) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(out) || misaligned(dout) || misaligned(dqkv)) return SLAPO_ERR_ALIGN;
-  const AttnShape as = {d->batch, d->seq, d->hidden, d->heads, d->causal};
+  const AttnShape as = make_attn_shape(d);
   launch_attn_bwd(d->dtype == SLAPO_FP32, as, qkv, seqlens, out, dout, lse, delta, dqkv, (hipStream_t)stream);
   return finish();
 }

@@ -115,6 +115,68 @@ __device__ __forceinline__ BlockId xcd_local_block() {
   return id;
 }
 
+// ---- dropout on the attention probabilities ---------------------------------------------------------
+// One Philox call yields the 16-bit draws of 8 consecutive keys of one query row (element index
+// ((b*heads + a)*S + i)*S + j, block = index >> 3; S % 8 == 0 keeps a block inside a row).
+//
+// Kernels whose lanes own a query (forward, dQ): a lane holds, per 32-key sub-tile, keys 8g + 4*(lane/32) + e
+// (g, e = 0..3) of its query, i.e. half of each of four blocks; lane^32 holds the other halves of the same
+// query. Each of the two computes two of the four blocks and hands the partner its half (two words per
+// block through the lane exchange). Returns bit r = element r of the 16-element accumulator is kept.
+__device__ __forceinline__ uint32_t keep16_query_lane(const DropoutParams& dp, uint64_t row_blk, int kvs, int kc) {
+  uint32_t lo[4], hi[4];   // per block g: the word holding e = 0,1 and the word holding e = 2,3 of this lane's half
+#pragma unroll
+  for (int gg = 0; gg < 2; ++gg) {
+    uint32_t o[4];
+    const uint64_t blk = row_blk + (uint64_t)((kvs >> 3) + 2 * kc + gg);
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), dp.site, dp.layer, dp.key0, dp.key1, o);
+    const uint32_t mine0 = kc ? o[2] : o[0], mine1 = kc ? o[3] : o[1];
+    const uint32_t send0 = kc ? o[0] : o[2], send1 = kc ? o[1] : o[3];
+    const uint32_t rcv0 = (uint32_t)__shfl_xor((int)send0, 32, 64), rcv1 = (uint32_t)__shfl_xor((int)send1, 32, 64);
+    lo[gg] = kc ? rcv0 : mine0;          // blocks 0, 1 are computed by the lanes with kc == 0
+    hi[gg] = kc ? rcv1 : mine1;
+    lo[2 + gg] = kc ? mine0 : rcv0;      // blocks 2, 3 by the lanes with kc == 1
+    hi[2 + gg] = kc ? mine1 : rcv1;
+  }
+  uint32_t bits = 0;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    bits |= ((lo[g] & 0xffffu) >= dp.thr ? 1u : 0u) << (4 * g);
+    bits |= ((lo[g] >> 16) >= dp.thr ? 1u : 0u) << (4 * g + 1);
+    bits |= ((hi[g] & 0xffffu) >= dp.thr ? 1u : 0u) << (4 * g + 2);
+    bits |= ((hi[g] >> 16) >= dp.thr ? 1u : 0u) << (4 * g + 3);
+  }
+  return bits;
+}
+
+// The dK/dV kernel's lanes own a key: element r of a 32-query sub-tile is query qs + 8*(r/4) + 4*(lane/32) + r%4
+// against the lane's key, so every element sits in a different block, and the 8 lanes whose keys share a block
+// (consecutive lanes) need the same 16 calls. Lane t of such a group computes the calls of elements 2t and
+// 2t+1, all eight exchange them through `xch` (per wavefront: [2 halves][4 groups][16 elements][4 words]), and
+// every lane picks the draw of its own key out of each call.
+__device__ __forceinline__ uint32_t keep16_key_lane(const DropoutParams& dp, uint64_t head_blk, int S8, int qs, int my_kv,
+                                                    int lane, uint32_t* xch) {
+  const int kc = lane >> 5, t = lane & 7, grp = (lane >> 3) & 7;   // grp: 4 groups per half, halves apart by 4
+  uint32_t* slot = xch + grp * 64;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int r = 2 * t + u;
+    const int q = qs + 8 * (r >> 2) + 4 * kc + (r & 3);
+    uint32_t o[4];
+    const uint64_t blk = head_blk + (uint64_t)q * (uint64_t)S8 + (uint64_t)(my_kv >> 3);
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), dp.site, dp.layer, dp.key0, dp.key1, o);
+    *reinterpret_cast<uint4*>(slot + r * 4) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // LDS writes of this wavefront done (lgkmcnt 0)
+  __builtin_amdgcn_wave_barrier();
+  const int word = (my_kv & 7) >> 1, sh16 = 16 * (my_kv & 1);
+  uint32_t bits = 0;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) bits |= (((slot[r * 4 + word] >> sh16) & 0xffffu) >= dp.thr ? 1u : 0u) << r;
+  __builtin_amdgcn_wave_barrier();      // the next call overwrites the slots
+  return bits;
+}
+
 // Tile pipeline shared by the three kernels: tile t is computed from LDS stage t&1 while the loads of
 // tiles t+1 and t+2 are in flight in two register sets. Loads and stores are issued on every step with a
 // clamped tile index (the surplus ones land in a stage nobody reads), so the number of loads in flight is
@@ -142,7 +204,7 @@ __device__ __forceinline__ BlockId xcd_local_block() {
   } while (0)
 
 // =================================== forward =====================================================
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                             const int32_t* __restrict__ seqlens,
                                                             bf16_t* __restrict__ out, float* __restrict__ lse) {
@@ -175,6 +237,7 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
   float m = -INFINITY, l = 0.f;   // running maximum (raw score units) and sum of this lane's half row
+  const uint64_t row_blk = ((((uint64_t)b * sh.heads + a) * S + (uint64_t)q_ld) * (uint64_t)S) >> 3;   // DROP: block of key 0
 
   TileRegs<D> rk[2], rv[2];
 #define FWD_LOAD(set, t) do { rk[set].load(base + H, rs, (t) * 64, S - 1, tid); rv[set].load(base + 2 * H, rs, (t) * 64, S - 1, tid); } while (0)
@@ -229,6 +292,14 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
         sc[i][r] = p;
         l += p;
       }
+    if (DROP) {   // the row sum above is the softmax denominator: dropout acts on the normalised probabilities
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const uint32_t keep = keep16_query_lane(sh.drop, row_blk, kv0 + 32 * i, kc);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[i][r] = ((keep >> r) & 1u) ? sc[i][r] : 0.f;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -244,7 +315,7 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
 #undef FWD_STORE
 
   const float l_tot = l + __shfl_xor(l, 32, 64);
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  const float inv = l_tot > 0.f ? (DROP ? sh.drop.scale : 1.f) / l_tot : 0.f;
   if (my_q < S) {
     bf16_t* orow = out + ((int64_t)b * S + my_q) * H + a * D;
 #pragma unroll
@@ -295,7 +366,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(AttnShape sh, const T* 
 }
 
 // ============================ backward: dK, dV per key tile ======================================
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                                  const int32_t* __restrict__ seqlens,
                                                                  const bf16_t* __restrict__ dout,
@@ -321,6 +392,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
   const int kv_ld = my_kv < S ? my_kv : S - 1;
   const int wave_kv_min = kv_base + 32 * wave;
   const bool wave_kv_edge = wave_kv_min + 32 > kv_len;   // some of this wave's keys are hidden
+  // DROP: block index of (query 0, key 0) of this head, and this wavefront's exchange area behind the stages
+  const uint64_t head_blk = ((((uint64_t)b * sh.heads + a) * S) * (uint64_t)S) >> 3;
+  uint32_t* xch = reinterpret_cast<uint32_t*>(smem + 2 * STAGE) + wave * 512;
   const float scale = rsqrtf((float)D), sl2 = LOG2E * scale;
 
   bf16x8_t kf[NS], vf[NS];
@@ -370,6 +444,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(dtile, fr_base, i * 32, s), vf[s], dp, 0, 0, 0);
       }
       const bool edge = wave_kv_edge || (qs + 32 > S) || (sh.causal && qs < wave_kv_min + 32);
+      uint32_t keep = 0xffffu;
+      if (DROP) keep = keep16_key_lane(sh.drop, head_blk, S >> 3, qs, kv_ld, lane, xch);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const float4 l4 = *reinterpret_cast<const float4*>(stats + i * 32 + g * 8 + 4 * kc);
@@ -384,8 +460,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
             const bool hide = (my_kv >= kv_len) | (q >= S) | ((sh.causal != 0) & (my_kv > q));
             p = hide ? 0.f : p;
           }
-          sc[r] = p;
-          dp[r] = p * (dp[r] - ds[e]);
+          float dpr = dp[r];
+          if (DROP) {
+            const bool kept = (keep >> r) & 1u;
+            dpr = kept ? dpr * sh.drop.scale : 0.f;          // dP = keep * (dO V^T) / (1 - p)
+            sc[r] = kept ? p * sh.drop.scale : 0.f;          // what multiplied V in the forward pass
+          } else {
+            sc[r] = p;
+          }
+          dp[r] = p * (dpr - ds[e]);
         }
       }
 #pragma unroll
@@ -422,7 +505,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
 }
 
 // ============================ backward: dQ per query tile ========================================
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                                const int32_t* __restrict__ seqlens,
                                                                const bf16_t* __restrict__ out,
@@ -456,6 +539,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
     df[s] = *reinterpret_cast<const bf16x8_t*>(dout + ((int64_t)b * S + q_ld) * H + a * D + 16 * s + 8 * kc);
   }
   const float my_lse2 = lse[((int64_t)b * sh.heads + a) * S + q_ld] * LOG2E;
+  const uint64_t row_blk = ((((uint64_t)b * sh.heads + a) * S + (uint64_t)q_ld) * (uint64_t)S) >> 3;   // DROP: block of key 0
   // delta = rowsum(dO * O) of this lane's query row: the lane holds half of the row's dO, lane^32 the other
   // half. It is also written out for the dK/dV kernel, which runs after this one.
   float my_delta = 0.f;
@@ -492,6 +576,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(kt, fr_base, i * 32, s), qf[s], sc, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(vt, fr_base, i * 32, s), df[s], dp, 0, 0, 0);
       }
+      uint32_t keep = 0xffffu;
+      if (DROP) keep = keep16_query_lane(sh.drop, row_blk, kv0 + 32 * i, kc);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -my_lse2));
@@ -500,6 +586,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
           const bool hide = (kv >= kv_len) | ((sh.causal != 0) & (kv > my_q));
           p = hide ? 0.f : p;
         }
+        if (DROP) dp[r] = ((keep >> r) & 1u) ? dp[r] * sh.drop.scale : 0.f;   // dP = keep * (dO V^T) / (1 - p)
         dp[r] = p * (dp[r] - my_delta);
       }
 #pragma unroll
@@ -559,10 +646,16 @@ __global__ __launch_bounds__(256) void attn_fwd_simple_kernel(AttnShape sh, cons
   }
   mx = wave_max(mx);
   float sum = 0.f;
-  for (int j = lane; j < kv_end; j += 64) { const float p = __expf(ps[j] - mx); ps[j] = p; sum += p; }
+  const bool drop = sh.drop.thr != 0;
+  const uint64_t e_row = (((uint64_t)b * sh.heads + a) * S + i) * S;   // element index of probability (i, 0)
+  for (int j = lane; j < kv_end; j += 64) {
+    const float p = __expf(ps[j] - mx);
+    sum += p;                                                         // the softmax is normalised before dropout
+    ps[j] = (drop && !dropout_keep1(sh.drop, e_row + j)) ? 0.f : p;
+  }
   sum = wave_sum(sum);
   __builtin_amdgcn_wave_barrier();
-  const float inv = sum > 0.f ? 1.f / sum : 0.f;
+  const float inv = sum > 0.f ? sh.drop.scale / sum : 0.f;
   for (int dd = lane; dd < D; dd += 64) {
     float acc = 0.f;
     for (int j = 0; j < kv_end; ++j) acc = fmaf(ps[j], to_f32(base[2 * H + j * rs + dd]), acc);
@@ -591,6 +684,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_simple_kernel(AttnShape sh, c
   if (sh.causal && i + 1 < kv_end) kv_end = i + 1;
   const float scale = rsqrtf((float)D);
   const float my_lse = lse[((int64_t)b * sh.heads + a) * S + i], my_delta = delta[((int64_t)b * sh.heads + a) * S + i];
+  const uint64_t e_row = (((uint64_t)b * sh.heads + a) * S + i) * S;
   for (int dd = lane; dd < D; dd += 64) {
     qs[dd] = to_f32(base[i * rs + dd]);
     dos[dd] = to_f32(dout[((int64_t)b * S + i) * H + a * D + dd]);
@@ -602,6 +696,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_simple_kernel(AttnShape sh, c
     float s = 0.f, dp = 0.f;
     for (int dd = 0; dd < D; ++dd) { s = fmaf(qs[dd], to_f32(kr[dd]), s); dp = fmaf(dos[dd], to_f32(vr[dd]), dp); }
     const float p = __expf(s * scale - my_lse);
+    if (sh.drop.thr != 0) dp = dropout_keep1(sh.drop, e_row + j) ? dp * sh.drop.scale : 0.f;
     ds[j] = p * (dp - my_delta);
   }
   __builtin_amdgcn_wave_barrier();
@@ -640,7 +735,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_simple_kernel(AttnShape sh,
     float s = 0.f, dp = 0.f;
     for (int dd = 0; dd < D; ++dd) { s = fmaf(to_f32(qr[dd]), ks[dd], s); dp = fmaf(to_f32(dr[dd]), vs[dd], dp); }
     const float p = __expf(s * scale - lse[((int64_t)b * sh.heads + a) * S + i]);
-    ps[i] = p;
+    float pv = p;   // what multiplies V in the forward pass
+    if (sh.drop.thr != 0) {
+      const bool keep = dropout_keep1(sh.drop, ((((uint64_t)b * sh.heads + a) * S + i) * S) + j);
+      pv = keep ? p * sh.drop.scale : 0.f;
+      dp = keep ? dp * sh.drop.scale : 0.f;
+    }
+    ps[i] = pv;
     ds[i] = p * (dp - delta[((int64_t)b * sh.heads + a) * S + i]);
   }
   __builtin_amdgcn_wave_barrier();
@@ -659,7 +760,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_simple_kernel(AttnShape sh,
 template <int D>
 static void fwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens, void* out, float* lse, hipStream_t st) {
   const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
-  auto kern = attn_fwd_bf16_kernel<D>;
+  auto kern = s.drop.thr ? attn_fwd_bf16_kernel<D, true> : attn_fwd_bf16_kernel<D, false>;
   (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3((s.seq + 127) / 128, s.heads, s.batch), dim3(256), lds, st, s, (const bf16_t*)qkv,
                      seqlens, (bf16_t*)out, lse);
@@ -686,14 +787,15 @@ static void bwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens
   dim3 grid((s.seq + 127) / 128, s.heads, s.batch);
   {  // dQ first: it also produces delta = rowsum(dO * O), which the dK/dV kernel reads
     const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
-    auto kern = attn_bwd_dq_bf16_kernel<D>;
+    auto kern = s.drop.thr ? attn_bwd_dq_bf16_kernel<D, true> : attn_bwd_dq_bf16_kernel<D, false>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)out,
                        (const bf16_t*)dout, lse, delta, (bf16_t*)dqkv);
   }
   {
-    const size_t lds = (size_t)2 * (2 * Tile<D>::ELEMS + 256) * sizeof(bf16_t);
-    auto kern = attn_bwd_dkdv_bf16_kernel<D>;
+    // with dropout: 2 KB per wavefront behind the stages for the exchange of mask draws
+    const size_t lds = (size_t)2 * (2 * Tile<D>::ELEMS + 256) * sizeof(bf16_t) + (s.drop.thr ? 4 * 2048 : 0);
+    auto kern = s.drop.thr ? attn_bwd_dkdv_bf16_kernel<D, true> : attn_bwd_dkdv_bf16_kernel<D, false>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)dout, lse,
                        (const float*)delta, (bf16_t*)dqkv);

@@ -127,4 +127,13 @@ __device__ __forceinline__ uint32_t dropout_keep8(const DropoutParams& dp, uint6
   return bits;
 }
 
+// Keep decision of the single element e (the plain kernels' per-element form of the same stream).
+__device__ __forceinline__ bool dropout_keep1(const DropoutParams& dp, uint64_t e) {
+  uint32_t o[4];
+  const uint64_t blk = e >> 3;
+  philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), dp.site, dp.layer, dp.key0, dp.key1, o);
+  const uint32_t j = (uint32_t)e & 7u;
+  return ((o[j >> 1] >> (16 * (j & 1))) & 0xffffu) >= dp.thr;
+}
+
 }  // namespace slapo

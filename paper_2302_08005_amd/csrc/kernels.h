@@ -14,6 +14,8 @@ void launch_gemm(int dtype_fp32, int layout, int epi, int act, int M, int N, int
 
 struct AttnShape {
   int batch, seq, hidden, heads, causal;
+  // dropout on the attention probabilities (site 2; element ((b*heads + a)*seq + i)*seq + j); thr == 0: none
+  DropoutParams drop = {0u, 0u, 2u, 0u, 0u, 1.0f};
 };
 void launch_attn_fwd(int dtype_fp32, const AttnShape& s, const void* qkv, const int32_t* seqlens, void* out,
                      float* lse, hipStream_t st);

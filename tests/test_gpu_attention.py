@@ -18,15 +18,22 @@ CASES = [
     (2, 256, 3, 64, 1, [256, 77], 8.0),       # causal + padding, large scores (online-softmax rescaling)
     (1, 384, 2, 128, 1, None, 1.0),
     (2, 136, 1, 128, 0, [100, 136], 4.0),
+    # with dropout on the attention probabilities (last entry): plain, causal + padding, d = 128 causal, padding
+    (2, 128, 2, 64, 0, None, 1.0, 0.2),
+    (2, 256, 3, 64, 1, [256, 77], 4.0, 0.1),
+    (1, 384, 2, 128, 1, None, 1.0, 0.3),
+    (3, 320, 2, 64, 0, [320, 8, 130], 1.0, 0.25),
 ]
 
 
 @pytest.mark.parametrize("dtype", [W.BF16, W.FP32])
 @pytest.mark.parametrize("case", CASES)
 def test_attention_fwd_bwd(dtype, case):
-    Bt, S, h, d, causal, sl, qs = case
+    Bt, S, h, d, causal, sl, qs = case[:7]
+    pd = case[7] if len(case) > 7 else 0.0
     H = h * d
-    cfg = W.LayerConfig("t", Bt, S, H, h, 64, causal=causal, dtype=dtype)
+    cfg = W.LayerConfig("t", Bt, S, H, h, 64, causal=causal, dtype=dtype, attn_dropout_p=pd,
+                        seed=0x5EED0000ABCD1234 if pd else 0, layer_id=3 if pd else 0)
     rng = np.random.default_rng(S + d + causal)
     qkv = rng.standard_normal((Bt * S, 3 * H))
     qkv[:, :H] *= qs

@@ -18,6 +18,12 @@ SMALL = [
     W.LayerConfig("ragged-bf16", 3, 200, 384, 6, 1000, causal=0, dropout_p=0.1, dtype=W.BF16, len_lo=50, len_hi=200, config_id=11),
     W.LayerConfig("d128-bf16-preln", 2, 264, 512, 4, 1536, causal=1, dropout_p=0.0, dtype=W.BF16, pre_ln=1, config_id=12),
     W.LayerConfig("d128-fp32", 1, 96, 256, 2, 520, causal=1, dropout_p=0.2, dtype=W.FP32, act=W.RELU, config_id=13),
+    # dropout on the attention probabilities as well (the layer's third mask stream)
+    W.CONFIGS["C1"].replace(name="c1-attn-dropout", attn_dropout_p=0.1),
+    W.LayerConfig("attn-dropout-bf16", 3, 200, 384, 6, 1000, causal=0, dropout_p=0.1, attn_dropout_p=0.15, dtype=W.BF16,
+                  len_lo=50, len_hi=200, layer_id=2, config_id=14),
+    W.LayerConfig("attn-dropout-bf16-preln-causal-d128", 2, 264, 512, 4, 1536, causal=1, dropout_p=0.1, attn_dropout_p=0.2,
+                  dtype=W.BF16, pre_ln=1, config_id=15),
 ]
 
 
@@ -97,7 +103,7 @@ def test_zero_dropout_matches_layer_without_dropout_bitwise():
     assert torch.equal(y, y2)
 
 
-@pytest.mark.parametrize("idx", [0, 2, 4])
+@pytest.mark.parametrize("idx", [0, 2, 4, 8])
 def test_checkpoint_mode_recomputes_to_the_same_bits(idx):
     """Activation checkpointing: no saved buffer, backward recomputes the forward; everything bit-identical."""
     cfg = SMALL[idx]
