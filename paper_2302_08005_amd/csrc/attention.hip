@@ -15,6 +15,8 @@
 // per key tile, dQ per query tile) so that no floating-point atomics are needed.
 //
 // fp32 path: one wavefront per row, plain loops (correctness mode).
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -446,31 +448,38 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
       const bool edge = wave_kv_edge || (qs + 32 > S) || (sh.causal && qs < wave_kv_min + 32);
       uint32_t keep = 0xffffu;
       if (DROP) keep = keep16_key_lane(sh.drop, head_blk, S >> 3, qs, kv_ld, lane, xch);
+      // two instances of the element loop, chosen by a wavefront-uniform branch: interior tiles carry no mask
+      // code at all (as one loop the compiler turns the test into a compare and a select on every element)
+      auto elements = [&](auto edge_tag) {
+        constexpr bool EDGE = decltype(edge_tag)::value;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 l4 = *reinterpret_cast<const float4*>(stats + i * 32 + g * 8 + 4 * kc);
-        const float4 d4 = *reinterpret_cast<const float4*>(stats + 64 + i * 32 + g * 8 + 4 * kc);
-        const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+        for (int g = 0; g < 4; ++g) {
+          const float4 l4 = *reinterpret_cast<const float4*>(stats + i * 32 + g * 8 + 4 * kc);
+          const float4 d4 = *reinterpret_cast<const float4*>(stats + 64 + i * 32 + g * 8 + 4 * kc);
+          const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * g + e;
-          float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -ls[e]));
-          if (edge) {   // uniform for the wavefront; the per-lane part is a select, not a branch
-            const int q = qs + g * 8 + 4 * kc + e;
-            const bool hide = (my_kv >= kv_len) | (q >= S) | ((sh.causal != 0) & (my_kv > q));
-            p = hide ? 0.f : p;
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * g + e;
+            float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -ls[e]));
+            if (EDGE) {   // the per-lane part is a select, not a branch
+              const int q = qs + g * 8 + 4 * kc + e;
+              const bool hide = (my_kv >= kv_len) | (q >= S) | ((sh.causal != 0) & (my_kv > q));
+              p = hide ? 0.f : p;
+            }
+            float dpr = dp[r];
+            if (DROP) {
+              const bool kept = (keep >> r) & 1u;
+              dpr = kept ? dpr * sh.drop.scale : 0.f;          // dP = keep * (dO V^T) / (1 - p)
+              sc[r] = kept ? p * sh.drop.scale : 0.f;          // what multiplied V in the forward pass
+            } else {
+              sc[r] = p;
+            }
+            dp[r] = p * (dpr - ds[e]);
           }
-          float dpr = dp[r];
-          if (DROP) {
-            const bool kept = (keep >> r) & 1u;
-            dpr = kept ? dpr * sh.drop.scale : 0.f;          // dP = keep * (dO V^T) / (1 - p)
-            sc[r] = kept ? p * sh.drop.scale : 0.f;          // what multiplied V in the forward pass
-          } else {
-            sc[r] = p;
-          }
-          dp[r] = p * (dpr - ds[e]);
         }
-      }
+      };
+      if (edge) elements(std::true_type{});
+      else elements(std::false_type{});
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const bf16x8_t pf = pack8(sc, h), dsf = pack8(dp, h);
@@ -578,17 +587,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
       }
       uint32_t keep = 0xffffu;
       if (DROP) keep = keep16_query_lane(sh.drop, row_blk, kv0 + 32 * i, kc);
+      auto elements = [&](auto edge_tag) {   // two instances: interior tiles carry no mask code
+        constexpr bool EDGE = decltype(edge_tag)::value;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -my_lse2));
-        if (edge) {
-          const int kv = kv0 + i * 32 + acc_row(r, lane);
-          const bool hide = (kv >= kv_len) | ((sh.causal != 0) & (kv > my_q));
-          p = hide ? 0.f : p;
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -my_lse2));
+          if (EDGE) {
+            const int kv = kv0 + i * 32 + acc_row(r, lane);
+            const bool hide = (kv >= kv_len) | ((sh.causal != 0) & (kv > my_q));
+            p = hide ? 0.f : p;
+          }
+          if (DROP) dp[r] = ((keep >> r) & 1u) ? dp[r] * sh.drop.scale : 0.f;   // dP = keep * (dO V^T) / (1 - p)
+          dp[r] = p * (dp[r] - my_delta);
         }
-        if (DROP) dp[r] = ((keep >> r) & 1u) ? dp[r] * sh.drop.scale : 0.f;   // dP = keep * (dO V^T) / (1 - p)
-        dp[r] = p * (dp[r] - my_delta);
-      }
+      };
+      if (edge) elements(std::true_type{});
+      else elements(std::false_type{});
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const bf16x8_t dsf = pack8(dp, h);
