@@ -173,7 +173,10 @@ def main():
         torch.cuda.synchronize()
     # for reference: the largest forward GEMM with its fused bias+activation epilogue (FFN1)
     y1 = layer.saved_tensor("n2" if cfg.pre_ln else "y1")
-    u = layer.saved_tensor("u")
+    try:
+        u = layer.saved_tensor("dact")
+    except Exception:          # a library built before the region was renamed (A/B runs through SLAPO_LIB)
+        u = layer.saved_tensor("u")
     g = torch.empty_like(u)
 
     def ffn1():

@@ -90,7 +90,7 @@ typedef struct {
 
 /* Sizes in bytes of the two caller-provided device buffers: `saved` carries activations from
  * slapo_layer_fwd to slapo_layer_bwd (QKV, attention output, logsumexp, pre-norm sums, LayerNorm
- * statistics, FFN pre-activation and activation) and must stay untouched in between; `scratch` is
+ * statistics, FFN activation and activation derivative) and must stay untouched in between; `scratch` is
  * free for reuse as soon as a call's work has completed on the stream (so one scratch buffer can serve
  * every layer of a stack). With desc->checkpoint = 1, saved_bytes is 0. */
 int slapo_layer_workspace(const slapo_layer_desc *desc, size_t *saved_bytes, size_t *scratch_bytes);
@@ -98,7 +98,7 @@ int slapo_layer_workspace(const slapo_layer_desc *desc, size_t *saved_bytes, siz
 /* Named regions inside `saved`, for tests and tools. Writes byte offset and byte length; returns
  * SLAPO_ERR_UNSUPPORTED if the region does not exist for this wiring. Names: "qkv" [T,3H], "attn"
  * [T,H], "lse" [B,heads,S] fp32, "z1" [T,H], "n1" (pre-LN) [T,H], "y1" (post-LN) / "n2" (pre-LN)
- * [T,H], "u" [T,F], "g" [T,F], "z2" (post-LN) [T,H], "mu1","rstd1","mu2","rstd2" [T] fp32. */
+ * [T,H], "dact" [T,F] (act'(u) of the FFN pre-activation u), "g" [T,F], "z2" (post-LN) [T,H], "mu1","rstd1","mu2","rstd2" [T] fp32. */
 int slapo_layer_saved_region(const slapo_layer_desc *desc, const char *name, size_t *offset, size_t *bytes);
 
 /* Forward of the scheduled layer (section 2.2 steps 1-2, appendix schedule):
@@ -145,8 +145,9 @@ const char *slapo_status_string(int status);
  *   layout 1 (NN): A [M,K], B [K,N]   -- input gradients dY W
  *   layout 2 (TN): A [K,M], B [K,N]   -- weight gradients dY^T X
  *   epilogue 0: C = acc                       1: C = acc + bias[n]
- *            2: aux_out = acc + bias[n]; C = act(aux_out)    (F.gelu(bias + x), appendix schedule)
- *            3: C = acc * act'(aux_in[m,n])   4: C = acc + aux_in[m,n]  (aux_in may alias C)
+ *            2: u = acc + bias[n]; C = act(u), aux_out = act'(u)   (F.gelu(bias + x), appendix schedule;
+ *               the derivative is all that backward needs of u, and its terms are at hand here)
+ *            3: C = acc * aux_in[m,n] (aux_in = the aux_out of epilogue 2)   4: C = acc + aux_in[m,n]  (aux_in may alias C)
  * M, N, K > 0; K-contiguous operands need K % 8 == 0, M/N-contiguous ones M % 8 / N % 8 == 0;
  * N % 8 == 0. */
 int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K,

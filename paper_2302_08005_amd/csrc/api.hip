@@ -186,7 +186,7 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
   else if (!strcmp(name, "n1")) { off = L.n1; len = T * H * eb; }
   else if (!strcmp(name, "y1") && !desc->pre_ln) { off = L.y1; len = T * H * eb; }
   else if (!strcmp(name, "n2") && desc->pre_ln) { off = L.y1; len = T * H * eb; }
-  else if (!strcmp(name, "u")) { off = L.u; len = T * F * eb; }
+  else if (!strcmp(name, "dact")) { off = L.u; len = T * F * eb; }
   else if (!strcmp(name, "g")) { off = L.g; len = T * F * eb; }
   else if (!strcmp(name, "z2")) { off = L.z2; len = T * H * eb; }
   else if (!strcmp(name, "mu1")) { off = L.mu1; len = T * 4; }

@@ -48,11 +48,6 @@ __device__ __forceinline__ GeluTerms gelu_terms(float u) {
   g.e = e;
   return g;
 }
-__device__ __forceinline__ float gelu_fast(float u) { return u * gelu_terms(u).phi; }
-__device__ __forceinline__ float gelu_grad_fast(float u) {
-  const GeluTerms g = gelu_terms(u);
-  return fmaf(u * g.e, 0.39894228040143268f, g.phi);
-}
 
 template <typename T>
 __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int64_t m, int64_t n, int64_t ldc,
@@ -64,12 +59,10 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
     v += to_f32(bias[n]);
   } else if (epi == EPI_BIAS_ACT) {
     v += to_f32(bias[n]);
-    T u;
-    from_f32(u, v);
-    aux_out[idx] = u;
-    v = act_fwd(to_f32(u), act);  // activation of the stored pre-activation, as backward will see it
+    from_f32(aux_out[idx], act_grad(v, act));   // all that backward needs of the pre-activation
+    v = act_fwd(v, act);
   } else if (epi == EPI_DACT) {
-    v *= act_grad(to_f32(aux_in[idx]), act);
+    v *= to_f32(aux_in[idx]);
   } else if (epi == EPI_ADD) {
     v += to_f32(aux_in[idx]);
   }
@@ -497,25 +490,26 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
         } else if (EPI == EPI_BIAS_ACT) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += bv[e];
-          store8(aux_out + idx, v);
-          // activation of the stored (rounded) pre-activation, the value backward will differentiate at
+          // Activation and its derivative from the same fp32 pre-activation; the derivative is what is kept
+          // for backward (the activation terms are at hand here, and backward is then one multiply).
+          float dv[8];
           if (act == ACT_RELU) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+            for (int e = 0; e < 8; ++e) { dv[e] = v[e] > 0.f ? 1.f : 0.f; v[e] = v[e] > 0.f ? v[e] : 0.f; }
           } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = gelu_fast(bf16_to_f32(f32_to_bf16(v[e])));
+            for (int e = 0; e < 8; ++e) {
+              const GeluTerms g = gelu_terms(v[e]);
+              dv[e] = fmaf(v[e] * g.e, 0.39894228040143268f, g.phi);
+              v[e] *= g.phi;
+            }
           }
+          store8(aux_out + idx, dv);
         } else if (EPI == EPI_DACT) {
           float u[8];
           aux_get(au[i][pass], u);
-          if (act == ACT_RELU) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = u[e] > 0.f ? v[e] : 0.f;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(u[e]);
-          }
+          for (int e = 0; e < 8; ++e) v[e] *= u[e];
         } else if (EPI == EPI_ADD) {
           float u[8];
           aux_get(au[i][pass], u);

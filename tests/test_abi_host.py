@@ -64,7 +64,7 @@ def test_saved_regions_are_disjoint_and_inside_the_buffer():
     for pre_ln in (0, 1):
         d = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024, pre_ln=pre_ln)
         saved, _ = B.slapo_layer_workspace(d)
-        names = ["qkv", "attn", "lse", "z1", "u", "g", "mu1", "rstd1", "mu2", "rstd2"]
+        names = ["qkv", "attn", "lse", "z1", "dact", "g", "mu1", "rstd1", "mu2", "rstd2"]
         names += ["n1", "n2"] if pre_ln else ["y1", "z2"]
         spans = sorted(B.slapo_layer_saved_region(d, n) for n in names)
         for (o0, b0), (o1, _) in zip(spans, spans[1:]):

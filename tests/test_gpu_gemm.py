@@ -6,7 +6,7 @@ from scipy.special import erf
 
 import workloads as W
 from paper_2302_08005_amd import binding as B
-from gpu_util import DEV, TOL, err, store, to_dev
+from gpu_util import DEV, TOL, err, store, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -58,10 +58,15 @@ def test_gemm_epilogues(dtype, act):
     U = torch.empty_like(Cout)
     B.slapo_gemm(dtype, B.NT, B.EPI_BIAS, act, M, N, K, A, Wt, Cout, bias=bd)
     assert err(Cout, acc + bias) <= tol
-    B.slapo_gemm(dtype, B.NT, B.EPI_BIAS_ACT, act, M, N, K, A, Wt, Cout, bias=bd, aux_out=U)
-    assert err(U, acc + bias) <= tol and err(Cout, _act(acc + bias, act)) <= tol
-    B.slapo_gemm(dtype, B.NT, B.EPI_DACT, act, M, N, K, A, Wt, Cout, aux_in=auxd)
-    assert err(Cout, acc * _dact(aux.astype(np.float64), act)) <= tol
+    B.slapo_gemm(dtype, B.NT, B.EPI_BIAS_ACT, act, M, N, K, A, Wt, Cout, bias=bd, aux_out=U)   # U receives act'(pre)
+    if act == W.GELU:   # (the ReLU gate is a 0/1 decision at pre = 0 +- rounding: compared where it is decided)
+        assert err(U, _dact(acc + bias, act)) <= tol
+    else:
+        clear = np.abs(acc + bias) > 1e-2
+        assert np.array_equal(to_np(U)[clear], _dact(acc + bias, act)[clear])
+    assert err(Cout, _act(acc + bias, act)) <= tol
+    B.slapo_gemm(dtype, B.NT, B.EPI_DACT, act, M, N, K, A, Wt, Cout, aux_in=auxd)                # C = acc * aux_in
+    assert err(Cout, acc * aux.astype(np.float64)) <= tol
     B.slapo_gemm(dtype, B.NT, B.EPI_ADD, act, M, N, K, A, Wt, Cout, aux_in=auxd)
     assert err(Cout, acc + aux) <= tol
     C2 = auxd.clone()                          # in-place accumulate (aux_in aliases C)

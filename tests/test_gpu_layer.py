@@ -34,7 +34,8 @@ def teacher_force(layer, cfg, ref):
     the stored pre-activation, so both sides must take it from the same stored values; an end-to-end
     run would flip the gate wherever the two forward passes differ by a rounding error around u = 0.
     """
-    names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "u": "U", "g": "G", "lse": "LSE", "mu1": "mu1", "rstd1": "rstd1",
+    ref = dict(ref, DACT=L._act_grad(ref["U"], cfg.act))   # the layer keeps act'(U), not U
+    names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "dact": "DACT", "g": "G", "lse": "LSE", "mu1": "mu1", "rstd1": "rstd1",
              "mu2": "mu2", "rstd2": "rstd2"}
     names.update({"n1": "N1", "n2": "N2"} if cfg.pre_ln else {"y1": "Y1", "z2": "Z2"})
     for k, rk in names.items():
@@ -55,7 +56,7 @@ def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True, teacher_forced_
     if teacher_forced_bwd:
         torch.cuda.synchronize()
         saved_errs = {"saved." + k: err(layer.saved_tensor(k).reshape(-1), ref[rk].reshape(-1))
-                      for k, rk in (("u", "U"), ("g", "G"), ("z1", "Z1"), ("qkv", "QKV"), ("attn", "A"))}
+                      for k, rk in (("g", "G"), ("z1", "Z1"), ("qkv", "QKV"), ("attn", "A"))}
         teacher_force(layer, cfg, ref)
     dx = layer.backward(xd, sld, dyd)
     torch.cuda.synchronize()
@@ -65,7 +66,10 @@ def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True, teacher_forced_
     if teacher_forced_bwd:
         errs.update(saved_errs)
     if check_saved:
-        names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "u": "U", "g": "G", "lse": "LSE"}
+        ref = dict(ref, DACT=L._act_grad(ref["U"], cfg.act))
+        names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "g": "G", "lse": "LSE"}
+        if cfg.act == W.GELU:   # (a ReLU gate is 0/1 and flips with the rounding of U around 0: not an error measure)
+            names["dact"] = "DACT"
         names.update({"n1": "N1", "n2": "N2"} if cfg.pre_ln else {"y1": "Y1", "z2": "Z2"})
         for k, rk in names.items():
             errs["saved." + k] = err(layer.saved_tensor(k).reshape(-1), ref[rk].reshape(-1))
