@@ -78,6 +78,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--checkpoint", action="store_true",
                     help="activation-checkpointing mode: nothing saved, backward recomputes the forward")
+    ap.add_argument("--fp16", action="store_true", help="IEEE half storage instead of bf16 (same kernels)")
     ap.add_argument("--attn-dropout", type=float, default=0.0,
                     help="also drop attention probabilities with this probability (0 = the benchmark configuration)")
     ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
@@ -94,10 +95,12 @@ def main():
     cfg = W.CONFIGS[args.config]
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
-    params = W.make_params(cfg)
-    x, dy, seqlens = W.make_inputs(cfg)
     if args.attn_dropout:
         cfg = cfg.replace(attn_dropout_p=args.attn_dropout)
+    if args.fp16:
+        cfg = cfg.replace(dtype=W.FP16)
+    params = W.make_params(cfg)
+    x, dy, seqlens = W.make_inputs(cfg)
     layer = B.Layer(cfg, params, checkpoint=1 if args.checkpoint else 0)
     xd, dyd = layer.to_device(x), layer.to_device(dy)
     sld = None if seqlens is None else torch.from_numpy(seqlens).cuda()
@@ -218,7 +221,7 @@ def main():
 
     out = {"metric": "layer fwd+bwd samples/s", "value": cfg.batch / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == W.BF16 else "f32",
+           "scaling": "weak", "vs_baseline": None, "dtype": {W.BF16: "bf16", W.FP16: "f16"}.get(cfg.dtype, "f32"),
            "data": "synthetic",
            "config": {"workload": cfg.name, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                       "heads": cfg.heads, "ffn": cfg.ffn, "causal": cfg.causal, "dropout_p": cfg.dropout_p,

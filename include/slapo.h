@@ -48,7 +48,7 @@ typedef enum {
   SLAPO_ERR_HIP = -6          /* a kernel launch reported an error                             */
 } slapo_status;
 
-enum { SLAPO_BF16 = 0, SLAPO_FP32 = 1 };
+enum { SLAPO_BF16 = 0, SLAPO_FP32 = 1, SLAPO_FP16 = 2 };   /* FP16: IEEE half storage, fp32 accumulation, same kernels */
 enum { SLAPO_GELU_ERF = 0, SLAPO_RELU = 1 };
 
 /* Layer description (host struct). hidden/heads must be 64 or 128; hidden, ffn multiples of 8;
@@ -59,7 +59,7 @@ typedef struct {
   float dropout_p;          /* probability of dropping, in [0,1); applied at the two fused
                                bias+dropout+residual sites (attention probabilities: see below) */
   uint64_t seed;            /* dropout seed (Philox key)                                       */
-  int32_t dtype;            /* SLAPO_BF16 | SLAPO_FP32: activations, weights and gradients     */
+  int32_t dtype;            /* SLAPO_BF16 | SLAPO_FP32 | SLAPO_FP16: activations, weights, gradients */
   int32_t act;              /* SLAPO_GELU_ERF (0.5 u (1 + erf(u/sqrt 2))) | SLAPO_RELU         */
   int32_t pre_ln;           /* 0: y = LN(x + f(x)) (BERT); 1: y = x + f(LN(x)) (GPT/OPT)       */
   int32_t layer_id;         /* mixed into the dropout counter so stacked layers differ         */

@@ -10,7 +10,7 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SLAPO_LIB", os.path.join(HERE, "libslapo_mi355x.so"))
 
-BF16, FP32 = 0, 1
+BF16, FP32, FP16 = 0, 1, 2
 GELU, RELU = 0, 1
 NT, NN, TN = 0, 1, 2
 EPI_NONE, EPI_BIAS, EPI_BIAS_ACT, EPI_DACT, EPI_ADD = 0, 1, 2, 3, 4
@@ -111,7 +111,7 @@ def make_desc(cfg=None, **kw) -> LayerDesc:
 
 
 def torch_dtype(desc: LayerDesc):
-    return torch.float32 if desc.dtype == FP32 else torch.bfloat16
+    return {FP32: torch.float32, FP16: torch.float16}.get(desc.dtype, torch.bfloat16)
 
 
 def slapo_layer_workspace(desc: LayerDesc):

@@ -25,7 +25,7 @@ int check_desc(const slapo_layer_desc* d) {
   const int hd = d->hidden / d->heads;
   if (hd != 64 && hd != 128) return SLAPO_ERR_UNSUPPORTED;
   if (d->hidden > 4096) return SLAPO_ERR_UNSUPPORTED;
-  if (d->dtype != SLAPO_BF16 && d->dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (d->dtype != SLAPO_BF16 && d->dtype != SLAPO_FP32 && d->dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (d->act != SLAPO_GELU_ERF && d->act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
   if ((d->causal != 0 && d->causal != 1) || (d->pre_ln != 0 && d->pre_ln != 1)) return SLAPO_ERR_UNSUPPORTED;
   if (d->checkpoint != 0 && d->checkpoint != 1) return SLAPO_ERR_UNSUPPORTED;
@@ -203,7 +203,7 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
 // backward, which is why it is a function of its own.
 static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
                         void* y, void* saved, void* scratch, hipStream_t st) {
-  const int f32 = d->dtype == SLAPO_FP32;
+  const int dt = d->dtype;   // SLAPO_* element types are the launch interface's DT_* values
   const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
   const SavedLayout L = saved_layout(d);
   const ScratchLayout W = scratch_layout(d);
@@ -219,21 +219,21 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   const void* attn_in = x;
   if (d->pre_ln) {
     void* n1 = sv + L.n1;
-    launch_bdrln_fwd(f32, T, H, nullptr, nullptr, x, p->ln1_g, p->ln1_b, nullptr, n1, mu1, rstd1, dp0, d->ln_eps, st);
+    launch_bdrln_fwd(dt, T, H, nullptr, nullptr, x, p->ln1_g, p->ln1_b, nullptr, n1, mu1, rstd1, dp0, d->ln_eps, st);
     attn_in = n1;
   }
-  launch_gemm(f32, GEMM_NT, EPI_BIAS, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
-  launch_attn_fwd(f32, as, qkv, seqlens, attn, lse, st);
-  launch_gemm(f32, GEMM_NT, EPI_NONE, d->act, T, H, H, attn, p->wo, r, nullptr, nullptr, nullptr, st);
-  if (d->pre_ln) launch_bdrln_fwd(f32, T, H, r, p->bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, st);
-  else launch_bdrln_fwd(f32, T, H, r, p->bo, x, p->ln1_g, p->ln1_b, z1, y1, mu1, rstd1, dp0, d->ln_eps, st);
-  launch_gemm(f32, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st);
-  launch_gemm(f32, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st);
+  launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
+  launch_attn_fwd(dt, as, qkv, seqlens, attn, lse, st);
+  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, H, attn, p->wo, r, nullptr, nullptr, nullptr, st);
+  if (d->pre_ln) launch_bdrln_fwd(dt, T, H, r, p->bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, st);
+  else launch_bdrln_fwd(dt, T, H, r, p->bo, x, p->ln1_g, p->ln1_b, z1, y1, mu1, rstd1, dp0, d->ln_eps, st);
+  launch_gemm(dt, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st);
+  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st);
   if (d->pre_ln) {
-    launch_bdrln_fwd(f32, T, H, r, p->b2, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, dp1, d->ln_eps, st);
+    launch_bdrln_fwd(dt, T, H, r, p->b2, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, dp1, d->ln_eps, st);
   } else {
     void* z2 = sv + L.z2;
-    launch_bdrln_fwd(f32, T, H, r, p->b2, y1, p->ln2_g, p->ln2_b, z2, y, mu2, rstd2, dp1, d->ln_eps, st);
+    launch_bdrln_fwd(dt, T, H, r, p->b2, y1, p->ln2_g, p->ln2_b, z2, y, mu2, rstd2, dp1, d->ln_eps, st);
   }
 }
 
@@ -263,7 +263,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(scratch) || (!d->checkpoint && misaligned(saved))) return SLAPO_ERR_ALIGN;
 
   hipStream_t st = (hipStream_t)stream;
-  const int f32 = d->dtype == SLAPO_FP32, acc = d->accumulate_grads ? 1 : 0;
+  const int dt = d->dtype, acc = d->accumulate_grads ? 1 : 0;
   const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
   const SavedLayout L = saved_layout(d);
   const ScratchLayout W = scratch_layout(d);
@@ -294,55 +294,55 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   };
   // weight gradient: C (+)= A^T B
   auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
-    launch_gemm(f32, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, ws);
+    launch_gemm(dt, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, ws);
   };
   auto colsum = [&](const void* a, int N, void* out, hipStream_t s) {
     float* part = s == st ? pcol2 : pcol;   // per stream, so that the two sums may run at the same time
-    launch_colsum_partials(f32, T, N, a, part, s);
-    launch_colreduce_partials(f32, ncol, N, N, part, out, acc, s);
+    launch_colsum_partials(dt, T, N, a, part, s);
+    launch_colreduce_partials(dt, ncol, N, N, part, out, acc, s);
   };
   auto reduce_rows = [&](void* dgamma, void* dbeta, void* dbias) {
-    launch_colreduce3(f32, nrow, H, prow, dgamma, dbeta, dbias, acc, st);
+    launch_colreduce3(dt, nrow, H, prow, dgamma, dbeta, dbias, acc, st);
   };
   // Buffers: t0 dZ2 -> dY1/dN2 -> dA -> dN1; t1 dR2 (kept for dW2); t2 dZ1; t3 dR1 (kept for dWo).
 
   // ---- FFN block ----
   if (d->pre_ln) {
-    launch_bdrln_bwd(f32, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, st);
+    launch_bdrln_bwd(dt, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, st);
     reduce_rows(nullptr, nullptr, gr->b2);
   } else {
-    launch_bdrln_bwd(f32, T, H, dy, sv + L.z2, mu2, rstd2, p->ln2_g, nullptr, t0, t1, prow, dp1, st);
+    launch_bdrln_bwd(dt, T, H, dy, sv + L.z2, mu2, rstd2, p->ln2_g, nullptr, t0, t1, prow, dp1, st);
     reduce_rows(gr->ln2_g, gr->ln2_b, gr->b2);
   }
   fork(0);
   dweight(H, F, t1, g, gr->w2);
-  launch_gemm(f32, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+  launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
   fork(1);
   colsum(du, F, gr->b1, ws);
   dweight(F, H, du, y1, gr->w1);
-  if (d->pre_ln) launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
-  else launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
+  if (d->pre_ln) launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
+  else launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
   // ---- attention block ----
   if (d->pre_ln) {
-    launch_bdrln_bwd(f32, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t3, prow, dp0, st);
+    launch_bdrln_bwd(dt, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t3, prow, dp0, st);
     reduce_rows(gr->ln2_g, gr->ln2_b, gr->bo);
   } else {
-    launch_bdrln_bwd(f32, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t3, prow, dp0, st);
+    launch_bdrln_bwd(dt, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t3, prow, dp0, st);
     reduce_rows(gr->ln1_g, gr->ln1_b, gr->bo);
   }
   fork(2);
   dweight(H, H, t3, attn, gr->wo);
-  launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
-  launch_attn_bwd(f32, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
+  launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
+  launch_attn_bwd(dt, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
   fork(3);
   if (d->pre_ln) {
     dweight(3 * H, H, dqkv, sv + L.n1, gr->wqkv);
-    launch_gemm(f32, GEMM_NN, EPI_NONE, d->act, T, H, 3 * H, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
-    launch_bdrln_bwd(f32, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, st);
+    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * H, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
+    launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, st);
     reduce_rows(gr->ln1_g, gr->ln1_b, nullptr);
   } else {
     dweight(3 * H, H, dqkv, x, gr->wqkv);
-    launch_gemm(f32, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
+    launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
   }
   // the last bias gradient goes behind the data gradient on the caller's stream: the helper stream's last
   // product is the longer one, and this way the two streams end at about the same time
@@ -415,7 +415,7 @@ int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
 
 int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
                const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
-  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_ADD) return SLAPO_ERR_UNSUPPORTED;
   if (act != SLAPO_GELU_ERF && act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
   if (M <= 0 || N <= 0 || K <= 0) return SLAPO_ERR_SHAPE;
@@ -428,7 +428,7 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
   if (layout == GEMM_TN ? (M % 8) : (K % 8)) return SLAPO_ERR_ALIGN;   // A's contiguous dimension
   if (layout == GEMM_NT && (K % 8)) return SLAPO_ERR_ALIGN;
   if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
-  launch_gemm(dtype == SLAPO_FP32, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
+  launch_gemm(dtype, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
               (hipStream_t)stream);
   return finish();
 }
@@ -440,7 +440,7 @@ int slapo_attn_fwd(const slapo_layer_desc* d, const void* qkv, const int32_t* se
   if (!qkv || !out || !lse) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(out)) return SLAPO_ERR_ALIGN;
   const AttnShape as = make_attn_shape(d);
-  launch_attn_fwd(d->dtype == SLAPO_FP32, as, qkv, seqlens, out, lse, (hipStream_t)stream);
+  launch_attn_fwd(d->dtype, as, qkv, seqlens, out, lse, (hipStream_t)stream);
   return finish();
 }
 
@@ -451,7 +451,7 @@ int slapo_attn_bwd(const slapo_layer_desc* d, const void* qkv, const int32_t* se
   if (!qkv || !out || !dout || !lse || !delta || !dqkv) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(out) || misaligned(dout) || misaligned(dqkv)) return SLAPO_ERR_ALIGN;
   const AttnShape as = make_attn_shape(d);
-  launch_attn_bwd(d->dtype == SLAPO_FP32, as, qkv, seqlens, out, dout, lse, delta, dqkv, (hipStream_t)stream);
+  launch_attn_bwd(d->dtype, as, qkv, seqlens, out, dout, lse, delta, dqkv, (hipStream_t)stream);
   return finish();
 }
 
@@ -467,7 +467,7 @@ int slapo_bdrln_fwd(const slapo_layer_desc* d, int site, int64_t T, const void* 
   if (!r && !gamma) return SLAPO_ERR_NULL;
   if (misaligned(r) || misaligned(bias) || misaligned(res) || misaligned(gamma) || misaligned(beta) ||
       misaligned(z_out) || misaligned(out)) return SLAPO_ERR_ALIGN;
-  launch_bdrln_fwd(d->dtype == SLAPO_FP32, T, d->hidden, r, bias, res, gamma, beta, z_out, out, mu, rstd,
+  launch_bdrln_fwd(d->dtype, T, d->hidden, r, bias, res, gamma, beta, z_out, out, mu, rstd,
                    make_dropout(d, site), d->ln_eps, (hipStream_t)stream);
   return finish();
 }
@@ -485,7 +485,7 @@ int slapo_bdrln_bwd(const slapo_layer_desc* d, int site, int64_t T, const void* 
   if (!dz_out && !dr_out) return SLAPO_ERR_NULL;
   if (misaligned(dout) || misaligned(z) || misaligned(gamma) || misaligned(dres_in) || misaligned(dz_out) ||
       misaligned(dr_out) || misaligned(partials)) return SLAPO_ERR_ALIGN;
-  launch_bdrln_bwd(d->dtype == SLAPO_FP32, T, d->hidden, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials,
+  launch_bdrln_bwd(d->dtype, T, d->hidden, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials,
                    make_dropout(d, site), (hipStream_t)stream);
   return finish();
 }
@@ -493,20 +493,20 @@ int slapo_bdrln_bwd(const slapo_layer_desc* d, int site, int64_t T, const void* 
 int slapo_colsum_blocks(int64_t T) { return colsum_blocks(T); }
 
 int slapo_colsum_partials(int dtype, int64_t T, int64_t N, const void* a, float* partials, void* stream) {
-  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (T <= 0 || N <= 0) return SLAPO_ERR_SHAPE;
   if (!a || !partials) return SLAPO_ERR_NULL;
   if (N % 8 || misaligned(a) || misaligned(partials)) return SLAPO_ERR_ALIGN;
-  launch_colsum_partials(dtype == SLAPO_FP32, T, N, a, partials, (hipStream_t)stream);
+  launch_colsum_partials(dtype, T, N, a, partials, (hipStream_t)stream);
   return finish();
 }
 
 int slapo_colreduce_partials(int dtype, int64_t nblk, int64_t stride, int64_t N, const float* partials, void* out,
                              int accumulate, void* stream) {
-  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32) return SLAPO_ERR_UNSUPPORTED;
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (nblk <= 0 || N <= 0 || stride < N) return SLAPO_ERR_SHAPE;
   if (!partials || !out) return SLAPO_ERR_NULL;
-  launch_colreduce_partials(dtype == SLAPO_FP32, nblk, stride, N, partials, out, accumulate, (hipStream_t)stream);
+  launch_colreduce_partials(dtype, nblk, stride, N, partials, out, accumulate, (hipStream_t)stream);
   return finish();
 }
 

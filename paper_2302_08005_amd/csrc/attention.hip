@@ -61,10 +61,11 @@ __device__ __forceinline__ bf16x8_t frag_tr(const bf16_t* tile, int base, int c0
   return __builtin_bit_cast(bf16x8_t, v);
 }
 // eight accumulator registers 8h..8h+7 as a bf16 operand
+template <bool F16>
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& v, int h) {
   uint4 w;
-  w.x = pack_bf16x2(v[8 * h + 0], v[8 * h + 1]); w.y = pack_bf16x2(v[8 * h + 2], v[8 * h + 3]);
-  w.z = pack_bf16x2(v[8 * h + 4], v[8 * h + 5]); w.w = pack_bf16x2(v[8 * h + 6], v[8 * h + 7]);
+  w.x = pack2<F16>(v[8 * h + 0], v[8 * h + 1]); w.y = pack2<F16>(v[8 * h + 2], v[8 * h + 3]);
+  w.z = pack2<F16>(v[8 * h + 4], v[8 * h + 5]); w.w = pack2<F16>(v[8 * h + 6], v[8 * h + 7]);
   return __builtin_bit_cast(bf16x8_t, w);
 }
 // row index inside a 32x32 accumulator tile of register r
@@ -206,7 +207,7 @@ __device__ __forceinline__ uint32_t keep16_key_lane(const DropoutParams& dp, uin
   } while (0)
 
 // =================================== forward =====================================================
-template <int D, bool DROP>
+template <int D, bool DROP, bool F16>
 __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                             const int32_t* __restrict__ seqlens,
                                                             bf16_t* __restrict__ out, float* __restrict__ lse) {
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
       for (int r = 0; r < 16; ++r) sc[i][r] = 0.f;
 #pragma unroll
       for (int s = 0; s < NS; ++s)
-        sc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(kt, fr_base, i * 32, s), qf[s], sc[i], 0, 0, 0);
+        sc[i] = mfma16<F16>(frag_rows<D>(kt, fr_base, i * 32, s), qf[s], sc[i]);
     }
     if ((kv0 + 64 > kv_len) || (sh.causal && kv0 + 63 > wave_q_min)) {   // tile crosses a mask boundary
 #pragma unroll
@@ -306,10 +307,10 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const bf16x8_t pf = pack8(sc[i], h);
+        const bf16x8_t pf = pack8<F16>(sc[i], h);
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(vt, ft_base, i * 32 + 16 * h, t), pf, o[t], 0, 0, 0);
+          o[t] = mfma16<F16>(frag_tr<D>(vt, ft_base, i * 32 + 16 * h, t), pf, o[t]);
       }
   };
   SLAPO_TILE_PIPELINE(n_tiles, FWD_LOAD, FWD_STORE, compute);
@@ -325,8 +326,8 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
-        w.x = pack_bf16x2(o[t][4 * g] * inv, o[t][4 * g + 1] * inv);
-        w.y = pack_bf16x2(o[t][4 * g + 2] * inv, o[t][4 * g + 3] * inv);
+        w.x = pack2<F16>(o[t][4 * g] * inv, o[t][4 * g + 1] * inv);
+        w.y = pack2<F16>(o[t][4 * g + 2] * inv, o[t][4 * g + 3] * inv);
         *reinterpret_cast<uint2*>(orow + t * 32 + g * 8 + 4 * kc) = w;
       }
     if (kc == 0) lse[((int64_t)b * sh.heads + a) * S + my_q] = l_tot > 0.f ? m * scale + __logf(l_tot) : -INFINITY;
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(AttnShape sh, const T* 
 }
 
 // ============================ backward: dK, dV per key tile ======================================
-template <int D, bool DROP>
+template <int D, bool DROP, bool F16>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                                  const int32_t* __restrict__ seqlens,
                                                                  const bf16_t* __restrict__ dout,
@@ -442,8 +443,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
       for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(qtile, fr_base, i * 32, s), kf[s], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(dtile, fr_base, i * 32, s), vf[s], dp, 0, 0, 0);
+        sc = mfma16<F16>(frag_rows<D>(qtile, fr_base, i * 32, s), kf[s], sc);
+        dp = mfma16<F16>(frag_rows<D>(dtile, fr_base, i * 32, s), vf[s], dp);
       }
       const bool edge = wave_kv_edge || (qs + 32 > S) || (sh.causal && qs < wave_kv_min + 32);
       uint32_t keep = 0xffffu;
@@ -482,11 +483,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
       else elements(std::false_type{});
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const bf16x8_t pf = pack8(sc, h), dsf = pack8(dp, h);
+        const bf16x8_t pf = pack8<F16>(sc, h), dsf = pack8<F16>(dp, h);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-          dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(dtile, ft_base, i * 32 + 16 * h, t), pf, dv[t], 0, 0, 0);
-          dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(qtile, ft_base, i * 32 + 16 * h, t), dsf, dk[t], 0, 0, 0);
+          dv[t] = mfma16<F16>(frag_tr<D>(dtile, ft_base, i * 32 + 16 * h, t), pf, dv[t]);
+          dk[t] = mfma16<F16>(frag_tr<D>(qtile, ft_base, i * 32 + 16 * h, t), dsf, dk[t]);
         }
       }
     }
@@ -503,18 +504,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
-        w.x = pack_bf16x2(dk[t][4 * g] * scale, dk[t][4 * g + 1] * scale);
-        w.y = pack_bf16x2(dk[t][4 * g + 2] * scale, dk[t][4 * g + 3] * scale);
+        w.x = pack2<F16>(dk[t][4 * g] * scale, dk[t][4 * g + 1] * scale);
+        w.y = pack2<F16>(dk[t][4 * g + 2] * scale, dk[t][4 * g + 3] * scale);
         *reinterpret_cast<uint2*>(krow + t * 32 + g * 8 + 4 * kc) = w;
-        w.x = pack_bf16x2(dv[t][4 * g], dv[t][4 * g + 1]);
-        w.y = pack_bf16x2(dv[t][4 * g + 2], dv[t][4 * g + 3]);
+        w.x = pack2<F16>(dv[t][4 * g], dv[t][4 * g + 1]);
+        w.y = pack2<F16>(dv[t][4 * g + 2], dv[t][4 * g + 3]);
         *reinterpret_cast<uint2*>(vrow + t * 32 + g * 8 + 4 * kc) = w;
       }
   }
 }
 
 // ============================ backward: dQ per query tile ========================================
-template <int D, bool DROP>
+template <int D, bool DROP, bool F16>
 __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                                const int32_t* __restrict__ seqlens,
                                                                const bf16_t* __restrict__ out,
@@ -555,8 +556,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     const bf16x8_t of = *reinterpret_cast<const bf16x8_t*>(out + ((int64_t)b * S + q_ld) * H + a * D + 16 * s + 8 * kc);
+    {
+      const u32x4_t ow = __builtin_bit_cast(u32x4_t, of), dw = __builtin_bit_cast(u32x4_t, df[s]);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) my_delta = fmaf((float)of[e], (float)df[s][e], my_delta);
+      for (int e = 0; e < 4; ++e) {
+        my_delta = fmaf(unpack_lo<F16>(ow[e]), unpack_lo<F16>(dw[e]), my_delta);
+        my_delta = fmaf(unpack_hi<F16>(ow[e]), unpack_hi<F16>(dw[e]), my_delta);
+      }
+    }
   }
   my_delta += __shfl_xor(my_delta, 32, 64);
   if (kc == 0 && my_q < S) delta[((int64_t)b * sh.heads + a) * S + my_q] = my_delta;
@@ -582,8 +589,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
       for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(kt, fr_base, i * 32, s), qf[s], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(vt, fr_base, i * 32, s), df[s], dp, 0, 0, 0);
+        sc = mfma16<F16>(frag_rows<D>(kt, fr_base, i * 32, s), qf[s], sc);
+        dp = mfma16<F16>(frag_rows<D>(vt, fr_base, i * 32, s), df[s], dp);
       }
       uint32_t keep = 0xffffu;
       if (DROP) keep = keep16_query_lane(sh.drop, row_blk, kv0 + 32 * i, kc);
@@ -605,10 +612,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
       else elements(std::false_type{});
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const bf16x8_t dsf = pack8(dp, h);
+        const bf16x8_t dsf = pack8<F16>(dp, h);
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-          dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<D>(kt, ft_base, i * 32 + 16 * h, t), dsf, dq[t], 0, 0, 0);
+          dq[t] = mfma16<F16>(frag_tr<D>(kt, ft_base, i * 32 + 16 * h, t), dsf, dq[t]);
       }
     }
   };
@@ -623,8 +630,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
-        w.x = pack_bf16x2(dq[t][4 * g] * scale, dq[t][4 * g + 1] * scale);
-        w.y = pack_bf16x2(dq[t][4 * g + 2] * scale, dq[t][4 * g + 3] * scale);
+        w.x = pack2<F16>(dq[t][4 * g] * scale, dq[t][4 * g + 1] * scale);
+        w.y = pack2<F16>(dq[t][4 * g + 2] * scale, dq[t][4 * g + 3] * scale);
         *reinterpret_cast<uint2*>(qrow + t * 32 + g * 8 + 4 * kc) = w;
       }
   }
@@ -771,10 +778,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_simple_kernel(AttnShape sh,
 }
 
 // =================================== launchers ===================================================
-template <int D>
+template <int D, bool F16>
 static void fwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens, void* out, float* lse, hipStream_t st) {
   const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
-  auto kern = s.drop.thr ? attn_fwd_bf16_kernel<D, true> : attn_fwd_bf16_kernel<D, false>;
+  auto kern = s.drop.thr ? attn_fwd_bf16_kernel<D, true, F16> : attn_fwd_bf16_kernel<D, false, F16>;
   (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3((s.seq + 127) / 128, s.heads, s.batch), dim3(256), lds, st, s, (const bf16_t*)qkv,
                      seqlens, (bf16_t*)out, lse);
@@ -788,20 +795,21 @@ static void fwd_f32(const AttnShape& s, const void* qkv, const int32_t* seqlens,
                      (float*)out, lse);
 }
 
-void launch_attn_fwd(int dtype_fp32, const AttnShape& s, const void* qkv, const int32_t* seqlens, void* out,
+void launch_attn_fwd(int dtype, const AttnShape& s, const void* qkv, const int32_t* seqlens, void* out,
                      float* lse, hipStream_t st) {
   const int D = s.hidden / s.heads;
-  if (dtype_fp32) { if (D == 64) fwd_f32<64>(s, qkv, seqlens, out, lse, st); else fwd_f32<128>(s, qkv, seqlens, out, lse, st); }
-  else { if (D == 64) fwd_bf16<64>(s, qkv, seqlens, out, lse, st); else fwd_bf16<128>(s, qkv, seqlens, out, lse, st); }
+  if (dtype == DT_FP32) { if (D == 64) fwd_f32<64>(s, qkv, seqlens, out, lse, st); else fwd_f32<128>(s, qkv, seqlens, out, lse, st); }
+  else if (dtype == DT_FP16) { if (D == 64) fwd_bf16<64, true>(s, qkv, seqlens, out, lse, st); else fwd_bf16<128, true>(s, qkv, seqlens, out, lse, st); }
+  else { if (D == 64) fwd_bf16<64, false>(s, qkv, seqlens, out, lse, st); else fwd_bf16<128, false>(s, qkv, seqlens, out, lse, st); }
 }
 
-template <int D>
+template <int D, bool F16>
 static void bwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens, const void* out, const void* dout,
                      const float* lse, float* delta, void* dqkv, hipStream_t st) {
   dim3 grid((s.seq + 127) / 128, s.heads, s.batch);
   {  // dQ first: it also produces delta = rowsum(dO * O), which the dK/dV kernel reads
     const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
-    auto kern = s.drop.thr ? attn_bwd_dq_bf16_kernel<D, true> : attn_bwd_dq_bf16_kernel<D, false>;
+    auto kern = s.drop.thr ? attn_bwd_dq_bf16_kernel<D, true, F16> : attn_bwd_dq_bf16_kernel<D, false, F16>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)out,
                        (const bf16_t*)dout, lse, delta, (bf16_t*)dqkv);
@@ -809,7 +817,7 @@ static void bwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens
   {
     // with dropout: 2 KB per wavefront behind the stages for the exchange of mask draws
     const size_t lds = (size_t)2 * (2 * Tile<D>::ELEMS + 256) * sizeof(bf16_t) + (s.drop.thr ? 4 * 2048 : 0);
-    auto kern = s.drop.thr ? attn_bwd_dkdv_bf16_kernel<D, true> : attn_bwd_dkdv_bf16_kernel<D, false>;
+    auto kern = s.drop.thr ? attn_bwd_dkdv_bf16_kernel<D, true, F16> : attn_bwd_dkdv_bf16_kernel<D, false, F16>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)dout, lse,
                        (const float*)delta, (bf16_t*)dqkv);
@@ -838,15 +846,18 @@ static void bwd_f32(const AttnShape& s, const void* qkv, const int32_t* seqlens,
   }
 }
 
-void launch_attn_bwd(int dtype_fp32, const AttnShape& s, const void* qkv, const int32_t* seqlens, const void* out,
+void launch_attn_bwd(int dtype, const AttnShape& s, const void* qkv, const int32_t* seqlens, const void* out,
                      const void* dout, const float* lse, float* delta, void* dqkv, hipStream_t st) {
   const int D = s.hidden / s.heads;
-  if (dtype_fp32) {
+  if (dtype == DT_FP32) {
     if (D == 64) bwd_f32<64>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
     else bwd_f32<128>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
+  } else if (dtype == DT_FP16) {
+    if (D == 64) bwd_bf16<64, true>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
+    else bwd_bf16<128, true>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
   } else {
-    if (D == 64) bwd_bf16<64>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
-    else bwd_bf16<128>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
+    if (D == 64) bwd_bf16<64, false>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
+    else bwd_bf16<128, false>(s, qkv, seqlens, out, dout, lse, delta, dqkv, st);
   }
 }
 

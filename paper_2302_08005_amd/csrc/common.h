@@ -14,7 +14,11 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
-typedef uint16_t bf16_t;  // storage type of a bf16 element
+typedef uint16_t bf16_t;  // storage of one 16-bit element: bf16, or IEEE half where a kernel is told so (F16 flag)
+typedef _Float16 f16_t;   // IEEE half as a type of its own, for the kernels that are templates of the element type
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+enum { DT_BF16 = 0, DT_FP32 = 1, DT_FP16 = 2 };   // element types of the launch interface (the C ABI's values)
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
@@ -27,12 +31,50 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 __device__ __forceinline__ bf16_t f32_to_bf16(float a) { return (bf16_t)(pack_bf16x2(a, 0.f) & 0xffffu); }
 
+// The two 16-bit formats behind one interface (F16 = IEEE half, else bf16): the hot kernels keep 16-bit data in
+// untyped containers (bf16_t storage, bf16x8_t fragments) and only these few operations know the format.
+template <bool F16> __device__ __forceinline__ uint32_t pack2(float a, float b) {   // round to nearest even; lo = a
+  if constexpr (F16) {
+    f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+  } else {
+    return pack_bf16x2(a, b);
+  }
+}
+template <bool F16> __device__ __forceinline__ float unpack_lo(uint32_t w) {
+  if constexpr (F16) return (float)__builtin_bit_cast(f16x2_t, w)[0];
+  else return bf16lo_to_f32(w);
+}
+template <bool F16> __device__ __forceinline__ float unpack_hi(uint32_t w) {
+  if constexpr (F16) return (float)__builtin_bit_cast(f16x2_t, w)[1];
+  else return bf16hi_to_f32(w);
+}
+template <bool F16> __device__ __forceinline__ f32x16_t mfma16(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+template <bool F16> __device__ __forceinline__ void load8h(const bf16_t* p, float (&v)[8]) {
+  const uint4 w = *reinterpret_cast<const uint4*>(p);
+  v[0] = unpack_lo<F16>(w.x); v[1] = unpack_hi<F16>(w.x); v[2] = unpack_lo<F16>(w.y); v[3] = unpack_hi<F16>(w.y);
+  v[4] = unpack_lo<F16>(w.z); v[5] = unpack_hi<F16>(w.z); v[6] = unpack_lo<F16>(w.w); v[7] = unpack_hi<F16>(w.w);
+}
+template <bool F16> __device__ __forceinline__ void store8h(bf16_t* p, const float (&v)[8]) {
+  uint4 w;
+  w.x = pack2<F16>(v[0], v[1]); w.y = pack2<F16>(v[2], v[3]);
+  w.z = pack2<F16>(v[4], v[5]); w.w = pack2<F16>(v[6], v[7]);
+  *reinterpret_cast<uint4*>(p) = w;
+}
+
 // Eight consecutive elements of either storage type <-> eight floats.
 __device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
   uint4 w = *reinterpret_cast<const uint4*>(p);
   v[0] = bf16lo_to_f32(w.x); v[1] = bf16hi_to_f32(w.x); v[2] = bf16lo_to_f32(w.y); v[3] = bf16hi_to_f32(w.y);
   v[4] = bf16lo_to_f32(w.z); v[5] = bf16hi_to_f32(w.z); v[6] = bf16lo_to_f32(w.w); v[7] = bf16hi_to_f32(w.w);
 }
+__device__ __forceinline__ void load8(const f16_t* p, float (&v)[8]) { load8h<true>(reinterpret_cast<const bf16_t*>(p), v); }
+__device__ __forceinline__ void store8(f16_t* p, const float (&v)[8]) { store8h<true>(reinterpret_cast<bf16_t*>(p), v); }
 __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
   float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
   v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
@@ -57,6 +99,14 @@ template <> struct Raw8<bf16_t> {
     v[4] = bf16lo_to_f32(w.z); v[5] = bf16hi_to_f32(w.z); v[6] = bf16lo_to_f32(w.w); v[7] = bf16hi_to_f32(w.w);
   }
 };
+template <> struct Raw8<f16_t> {
+  uint4 w;
+  __device__ __forceinline__ void load(const f16_t* p) { w = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    v[0] = unpack_lo<true>(w.x); v[1] = unpack_hi<true>(w.x); v[2] = unpack_lo<true>(w.y); v[3] = unpack_hi<true>(w.y);
+    v[4] = unpack_lo<true>(w.z); v[5] = unpack_hi<true>(w.z); v[6] = unpack_lo<true>(w.w); v[7] = unpack_hi<true>(w.w);
+  }
+};
 template <> struct Raw8<float> {
   float4 a, b;
   __device__ __forceinline__ void load(const float* p) {
@@ -67,8 +117,10 @@ template <> struct Raw8<float> {
   }
 };
 __device__ __forceinline__ float to_f32(bf16_t h) { return bf16_to_f32(h); }
+__device__ __forceinline__ float to_f32(f16_t h) { return (float)h; }
 __device__ __forceinline__ float to_f32(float f) { return f; }
 __device__ __forceinline__ void from_f32(bf16_t& d, float f) { d = f32_to_bf16(f); }
+__device__ __forceinline__ void from_f32(f16_t& d, float f) { d = (f16_t)f; }
 __device__ __forceinline__ void from_f32(float& d, float f) { d = f; }
 
 // Sum over the 64 lanes, returned to every lane. Data-parallel-primitive moves (quad permutes, mirrors inside

@@ -112,7 +112,9 @@ __device__ __forceinline__ void block_barrier() {        // barrier without the 
 //     vector-memory instruction holds its wavefront at issue while the address unit is busy, and the 32 KB
 //     a 128x128 tile needs per slab keep that unit (64 B per clock) busy for as long as the slab's MFMAs
 //     take; with the loads on wavefronts of their own, that wait never stands in front of an MFMA.
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, int NS, int PW, bool KTAIL, int EPI>
+// F16: the 16-bit elements are IEEE half instead of bf16 (same data movement; MFMA and conversions differ).
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, int NS, int PW, bool KTAIL, int EPI,
+          bool F16 = false>
 __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(int M, int N, int K,
                                                                   const bf16_t* __restrict__ A,
                                                                   const bf16_t* __restrict__ B,
@@ -334,7 +336,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma16<F16>(fa[i], fb[j], acc[i][j]);
     }
   };
 
@@ -444,7 +446,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   const int cc = lane % CPR, rr = lane / CPR;
   const int n = n0 + wn0 + cc * 8;
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if ((EPI == EPI_BIAS || EPI == EPI_BIAS_ACT) && n < N) load8(bias + n, bv);
+  if ((EPI == EPI_BIAS || EPI == EPI_BIAS_ACT) && n < N) load8h<F16>(bias + n, bv);
   // The auxiliary input of a 32-row slab is fetched one slab ahead (clamped addresses, so the loads are
   // unconditional): its latency passes while the slab before it is staged and written out.
   constexpr bool AUX = (EPI == EPI_DACT || EPI == EPI_ADD);
@@ -461,7 +463,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   };
   auto aux_get = [](const u32x4_t& w, float (&u)[8]) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { u[2 * e] = bf16lo_to_f32(w[e]); u[2 * e + 1] = bf16hi_to_f32(w[e]); }
+    for (int e = 0; e < 4; ++e) { u[2 * e] = unpack_lo<F16>(w[e]); u[2 * e + 1] = unpack_hi<F16>(w[e]); }
   };
   if (AUX) aux_fetch(0, au[0]);
 #pragma unroll
@@ -504,7 +506,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
               v[e] *= g.phi;
             }
           }
-          store8(aux_out + idx, dv);
+          store8h<F16>(aux_out + idx, dv);
         } else if (EPI == EPI_DACT) {
           float u[8];
           aux_get(au[i][pass], u);
@@ -516,7 +518,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += u[e];
         }
-        store8(C + idx, v);
+        store8h<F16>(C + idx, v);
       }
     }
   }
@@ -582,7 +584,7 @@ constexpr bool epi_used(int layout, int epi) {
                            : (epi == EPI_NONE || epi == EPI_ADD);
 }
 
-template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, int NS, int PW, bool KTAIL>
+template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, int NS, int PW, bool KTAIL, bool F16>
 static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                              const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
@@ -590,13 +592,13 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 #define SLAPO_GEMM(E)                                                                                       \
   do {                                                                                                      \
     if constexpr (KTAIL || epi_used(LAYOUT, E)) {                                                           \
-      auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, BK, WGM, WGN, KS, PF, NS, PW, KTAIL, E>;                           \
+      auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, BK, WGM, WGN, KS, PF, NS, PW, KTAIL, E, F16>;                           \
       (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
       hipLaunchKernelGGL(kern, dim3(tiles), dim3((WGM * WGN * KS + PW) * 64), lds, st, M, N, K, (const bf16_t*)A,       \
                          (const bf16_t*)B, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)aux_in,          \
                          (bf16_t*)aux_out, act);                                                            \
     } else {                                                                                                \
-      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true>(epi, act, M, N, K, A, B, C, bias, aux_in,    \
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true, F16>(epi, act, M, N, K, A, B, C, bias, aux_in,    \
                                                               aux_out, st);                                 \
     }                                                                                                       \
   } while (0)
@@ -617,28 +619,28 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 // tiles: long K the same direct scheme with four computing wavefronts, else 128-deep slabs and two wave
 // sets splitting each slab. Other K go to the general kernel (one slab of register prefetch, zero-filled
 // tail).
-template <int LAYOUT>
+template <int LAYOUT, bool F16>
 static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                         const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
   const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
   if (K % 128 == 0 && t256 >= 192)
-    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 256 == 0 && t128 >= 160)
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 128 == 0 && (t128 >= 160 || K % 256 != 0))
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 0, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 0, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 256 == 0 && K >= 1024)
-    launch_bf16_tile<LAYOUT, 128, 64, 64, 2, 2, 1, 2, 4, 4, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 64, 64, 2, 2, 1, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 256 == 0)
-    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, 0, 0, false>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, 0, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
 }
 
-void launch_gemm(int dtype_fp32, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
+void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
                  void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
-  if (dtype_fp32) {
+  if (dtype == DT_FP32) {
     dim3 grid((N + 63) / 64, (M + 63) / 64);
 #define SLAPO_F32(L)                                                                                      \
   hipLaunchKernelGGL(gemm_f32_kernel<L>, grid, dim3(256), 0, st, M, N, K, (const float*)A, (const float*)B, \
@@ -649,9 +651,12 @@ void launch_gemm(int dtype_fp32, int layout, int epi, int act, int M, int N, int
 #undef SLAPO_F32
     return;
   }
-  if (layout == GEMM_NT) launch_bf16<GEMM_NT>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (layout == GEMM_NN) launch_bf16<GEMM_NN>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else launch_bf16<GEMM_TN>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+#define SLAPO_H(F)                                                                                          \
+  if (layout == GEMM_NT) launch_bf16<GEMM_NT, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);     \
+  else if (layout == GEMM_NN) launch_bf16<GEMM_NN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); \
+  else launch_bf16<GEMM_TN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st)
+  if (dtype == DT_FP16) { SLAPO_H(true); } else { SLAPO_H(false); }
+#undef SLAPO_H
 }
 
 }  // namespace slapo

@@ -320,7 +320,7 @@ static void launch_fwd(int64_t rows, int H, const void* r, const void* bias, con
 #undef SLAPO_FWD
 }
 
-void launch_bdrln_fwd(int dtype_fp32, int64_t rows, int H, const void* r, const void* bias, const void* res,
+void launch_bdrln_fwd(int dtype, int64_t rows, int H, const void* r, const void* bias, const void* res,
                       const void* gamma, const void* beta, void* z_out, void* out, float* mu, float* rstd,
                       const DropoutParams& dp, float eps, hipStream_t st) {
   const bool bdr = r != nullptr, ln = gamma != nullptr;
@@ -328,7 +328,7 @@ void launch_bdrln_fwd(int dtype_fp32, int64_t rows, int H, const void* r, const 
   if (bdr && ln) launch_fwd<T, true, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st); \
   else if (bdr) launch_fwd<T, true, false>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st); \
   else launch_fwd<T, false, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st)
-  if (dtype_fp32) { SLAPO_PICK(float); } else { SLAPO_PICK(bf16_t); }
+  if (dtype == DT_FP32) { SLAPO_PICK(float); } else if (dtype == DT_FP16) { SLAPO_PICK(f16_t); } else { SLAPO_PICK(bf16_t); }
 #undef SLAPO_PICK
 }
 
@@ -360,17 +360,15 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
 #undef SLAPO_BWD
 }
 
-void launch_bdrln_bwd(int dtype_fp32, int64_t rows, int H, const void* dout, const void* z, const float* mu,
+void launch_bdrln_bwd(int dtype, int64_t rows, int H, const void* dout, const void* z, const float* mu,
                       const float* rstd, const void* gamma, const void* dres_in, void* dz_out, void* dr_out,
                       float* partials, const DropoutParams& dp, hipStream_t st) {
   const bool ln = gamma != nullptr;
-  if (dtype_fp32) {
-    if (ln) launch_bwd<float, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
-    else launch_bwd<float, false>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
-  } else {
-    if (ln) launch_bwd<bf16_t, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
-    else launch_bwd<bf16_t, false>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);
-  }
+#define SLAPO_PICK(T)                                                                                          \
+  if (ln) launch_bwd<T, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);     \
+  else launch_bwd<T, false>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st)
+  if (dtype == DT_FP32) { SLAPO_PICK(float); } else if (dtype == DT_FP16) { SLAPO_PICK(f16_t); } else { SLAPO_PICK(bf16_t); }
+#undef SLAPO_PICK
 }
 
 int colsum_blocks(int64_t rows) {
@@ -378,17 +376,19 @@ int colsum_blocks(int64_t rows) {
   return (int)(b > 64 ? 64 : (b < 1 ? 1 : b));
 }
 
-void launch_colsum_partials(int dtype_fp32, int64_t rows, int64_t N, const void* a, float* partials,
+void launch_colsum_partials(int dtype, int64_t rows, int64_t N, const void* a, float* partials,
                             hipStream_t st) {
   dim3 grid((unsigned)((N / 8 + 31) / 32), (unsigned)colsum_blocks(rows));
-  if (dtype_fp32) hipLaunchKernelGGL(colsum_partials_kernel<float>, grid, dim3(256), 0, st, rows, N, (const float*)a, partials);
+  if (dtype == DT_FP32) hipLaunchKernelGGL(colsum_partials_kernel<float>, grid, dim3(256), 0, st, rows, N, (const float*)a, partials);
+  else if (dtype == DT_FP16) hipLaunchKernelGGL(colsum_partials_kernel<f16_t>, grid, dim3(256), 0, st, rows, N, (const f16_t*)a, partials);
   else hipLaunchKernelGGL(colsum_partials_kernel<bf16_t>, grid, dim3(256), 0, st, rows, N, (const bf16_t*)a, partials);
 }
 
-void launch_colreduce_partials(int dtype_fp32, int64_t nblk, int64_t stride, int64_t N, const float* partials,
+void launch_colreduce_partials(int dtype, int64_t nblk, int64_t stride, int64_t N, const float* partials,
                                void* out, int accumulate, hipStream_t st) {
   dim3 grid((unsigned)((N + 63) / 64));
-  if (dtype_fp32) hipLaunchKernelGGL(colreduce_partials_kernel<float>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (float*)out, accumulate);
+  if (dtype == DT_FP32) hipLaunchKernelGGL(colreduce_partials_kernel<float>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (float*)out, accumulate);
+  else if (dtype == DT_FP16) hipLaunchKernelGGL(colreduce_partials_kernel<f16_t>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (f16_t*)out, accumulate);
   else hipLaunchKernelGGL(colreduce_partials_kernel<bf16_t>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (bf16_t*)out, accumulate);
 }
 
@@ -428,10 +428,11 @@ __global__ __launch_bounds__(1024) void colreduce3_kernel(int64_t nblk, int H, c
   }
 }
 
-void launch_colreduce3(int dtype_fp32, int64_t nblk, int H, const float* partials, void* out0, void* out1, void* out2,
+void launch_colreduce3(int dtype, int64_t nblk, int H, const float* partials, void* out0, void* out1, void* out2,
                        int accumulate, hipStream_t st) {
   dim3 grid((unsigned)((H + 63) / 64), 3);
-  if (dtype_fp32) hipLaunchKernelGGL(colreduce3_kernel<float>, grid, dim3(1024), 0, st, nblk, H, partials, (float*)out0, (float*)out1, (float*)out2, accumulate);
+  if (dtype == DT_FP32) hipLaunchKernelGGL(colreduce3_kernel<float>, grid, dim3(1024), 0, st, nblk, H, partials, (float*)out0, (float*)out1, (float*)out2, accumulate);
+  else if (dtype == DT_FP16) hipLaunchKernelGGL(colreduce3_kernel<f16_t>, grid, dim3(1024), 0, st, nblk, H, partials, (f16_t*)out0, (f16_t*)out1, (f16_t*)out2, accumulate);
   else hipLaunchKernelGGL(colreduce3_kernel<bf16_t>, grid, dim3(1024), 0, st, nblk, H, partials, (bf16_t*)out0, (bf16_t*)out1, (bf16_t*)out2, accumulate);
 }
 

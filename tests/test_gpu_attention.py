@@ -26,7 +26,7 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("dtype", [W.BF16, W.FP32])
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP32, W.FP16])
 @pytest.mark.parametrize("case", CASES)
 def test_attention_fwd_bwd(dtype, case):
     Bt, S, h, d, causal, sl, qs = case[:7]

@@ -27,7 +27,7 @@ SHAPES = [(256, 256, 128), (296, 264, 200), (128, 128, 64), (1024, 768, 512), (5
           (1664, 1672, 2048), (3592, 3336, 256), (520, 136, 2048)]
 
 
-@pytest.mark.parametrize("dtype", [W.BF16, W.FP32])
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP32, W.FP16])
 @pytest.mark.parametrize("layout", [B.NT, B.NN, B.TN])
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_gemm_layouts(dtype, layout, M, N, K):
@@ -39,10 +39,10 @@ def test_gemm_layouts(dtype, layout, M, N, K):
     Bm = to_dev(b.T.copy() if layout == B.NT else b, dtype)
     Cout = torch.empty(M, N, dtype=A.dtype, device=DEV)
     B.slapo_gemm(dtype, layout, B.EPI_NONE, 0, M, N, K, A, Bm, Cout)
-    assert err(Cout, ref) <= (5e-3 if dtype == W.BF16 else 1e-5)
+    assert err(Cout, ref) <= {W.BF16: 5e-3, W.FP16: 1e-3}.get(dtype, 1e-5)
 
 
-@pytest.mark.parametrize("dtype", [W.BF16, W.FP32])
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP32, W.FP16])
 @pytest.mark.parametrize("act", [W.GELU, W.RELU])
 def test_gemm_epilogues(dtype, act):
     M, N, K = 392, 520, 256

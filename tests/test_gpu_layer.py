@@ -18,6 +18,10 @@ SMALL = [
     W.LayerConfig("ragged-bf16", 3, 200, 384, 6, 1000, causal=0, dropout_p=0.1, dtype=W.BF16, len_lo=50, len_hi=200, config_id=11),
     W.LayerConfig("d128-bf16-preln", 2, 264, 512, 4, 1536, causal=1, dropout_p=0.0, dtype=W.BF16, pre_ln=1, config_id=12),
     W.LayerConfig("d128-fp32", 1, 96, 256, 2, 520, causal=1, dropout_p=0.2, dtype=W.FP32, act=W.RELU, config_id=13),
+    # IEEE half storage (the precision of the paper's own runs)
+    W.CONFIGS["C1"].replace(name="c1-fp16", dtype=W.FP16),
+    W.LayerConfig("fp16-preln-causal-d128-attn-dropout", 2, 264, 512, 4, 1536, causal=1, dropout_p=0.1, attn_dropout_p=0.1,
+                  dtype=W.FP16, pre_ln=1, act=W.GELU, config_id=16),
     # dropout on the attention probabilities as well (the layer's third mask stream)
     W.CONFIGS["C1"].replace(name="c1-attn-dropout", attn_dropout_p=0.1),
     W.LayerConfig("attn-dropout-bf16", 3, 200, 384, 6, 1000, causal=0, dropout_p=0.1, attn_dropout_p=0.15, dtype=W.BF16,
@@ -107,7 +111,7 @@ def test_zero_dropout_matches_layer_without_dropout_bitwise():
     assert torch.equal(y, y2)
 
 
-@pytest.mark.parametrize("idx", [0, 2, 4, 8])
+@pytest.mark.parametrize("idx", [0, 2, 4, 10])
 def test_checkpoint_mode_recomputes_to_the_same_bits(idx):
     """Activation checkpointing: no saved buffer, backward recomputes the forward; everything bit-identical."""
     cfg = SMALL[idx]
@@ -127,10 +131,12 @@ def test_checkpoint_mode_recomputes_to_the_same_bits(idx):
     assert all(v <= tol for v in errs.values()), errs
 
 
-@pytest.mark.parametrize("key", ["C2", "C3", "C4"])
+@pytest.mark.parametrize("key", ["C2", "C3", "C4", "C2-fp16"])
 def test_layer_parity_full_size(key):
     """The benchmark shapes themselves, in the launch configuration bench.py times."""
-    cfg = W.CONFIGS[key]
+    cfg = W.CONFIGS[key[:2]]
+    if key.endswith("-fp16"):
+        cfg = cfg.replace(name=key, dtype=W.FP16)
     # forward end to end; backward end to end too, except for bf16 ReLU layers (see teacher_force)
     errs, _, _ = run_case(cfg, perturbed=False, check_saved=False, teacher_forced_bwd=(cfg.act == W.RELU))
     tol = TOL[cfg.dtype]

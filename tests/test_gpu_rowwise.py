@@ -8,7 +8,7 @@ import workloads as W
 from oracle import layer as L
 from oracle import philox
 from paper_2302_08005_amd import binding as B
-from gpu_util import DEV, TOL, err, store, to_dev, to_np
+from gpu_util import DEV, TOL, err, store, tdtype, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -31,13 +31,13 @@ def _ref_fwd(r, bias, res, gamma, beta, keep, p, eps):
     return z, y, mu, rstd
 
 
-@pytest.mark.parametrize("dtype", [W.FP32, W.BF16])
+@pytest.mark.parametrize("dtype", [W.FP32, W.BF16, W.FP16])
 @pytest.mark.parametrize("T,H", [(37, 256), (515, 1024), (130, 2560), (64, 4096), (9, 64)])
 def test_bdrln_forward_and_backward(dtype, T, H):
     rng = np.random.default_rng(T * 7 + H)
     p, seed, site, layer = 0.1, 11, 1, 5
     d = B.make_desc(batch=1, seq=T, hidden=H, heads=H // 64, ffn=64, dropout_p=p, seed=seed, layer_id=layer, dtype=dtype)
-    dt = torch.float32 if dtype == W.FP32 else torch.bfloat16
+    dt = tdtype(dtype)
     r, res, dy, dres = (store(rng.standard_normal((T, H)), dtype) for _ in range(4))
     bias, beta = (store(rng.standard_normal(H) * 0.1, dtype) for _ in range(2))
     gamma = store(1.0 + rng.standard_normal(H) * 0.1, dtype)
@@ -88,14 +88,14 @@ def test_bdrln_forward_and_backward(dtype, T, H):
     assert err(dr, dy.astype(np.float64) * keep / (1.0 - p)) <= tol
 
 
-@pytest.mark.parametrize("dtype", [W.FP32, W.BF16])
+@pytest.mark.parametrize("dtype", [W.FP32, W.BF16, W.FP16])
 @pytest.mark.parametrize("T,N", [(100, 264), (4096, 3072), (33, 8)])
 def test_column_sums(dtype, T, N):
     rng = np.random.default_rng(3)
     a = store(rng.standard_normal((T, N)), dtype)
     nblk = B.slapo_colsum_blocks(T)
     part = torch.empty(nblk, N, dtype=torch.float32, device=DEV)
-    dt = torch.float32 if dtype == W.FP32 else torch.bfloat16
+    dt = tdtype(dtype)
     out = torch.ones(N, dtype=dt, device=DEV)
     B.slapo_colsum_partials(dtype, T, N, to_dev(a, dtype), part)
     B.slapo_colreduce_partials(dtype, nblk, N, N, part, out, 0)

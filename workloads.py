@@ -13,7 +13,7 @@ import dataclasses
 import numpy as np
 
 GELU, RELU = 0, 1
-BF16, FP32 = 0, 1
+BF16, FP32, FP16 = 0, 1, 2
 
 
 @dataclasses.dataclass(frozen=True)
@@ -106,6 +106,8 @@ def _store(cfg: LayerConfig, a: np.ndarray) -> np.ndarray:
     a = a.astype(np.float32)
     if cfg.dtype == BF16:
         a = round_to_bf16(a)
+    elif cfg.dtype == FP16:
+        a = a.astype(np.float16).astype(np.float32)   # IEEE half, round to nearest even
     return a
 
 
