@@ -43,7 +43,7 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_fwd_kernel(
             if (LN && sizeof(T) == 2) {
               // statistics are taken of the stored (rounded) sum, the value backward will read
 #pragma unroll
-              for (int j = 0; j < 8; ++j) v[i][j] = bf16_to_f32(f32_to_bf16(v[i][j]));
+              for (int j = 0; j < 8; ++j) { T h; from_f32(h, v[i][j]); v[i][j] = to_f32(h); }
             }
           }
         }
