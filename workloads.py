@@ -14,6 +14,7 @@ import numpy as np
 
 GELU, RELU = 0, 1
 BF16, FP32, FP16 = 0, 1, 2
+CLASSIC, LLAMA = 0, 1   # layer family: LayerNorm/bias/GeLU-or-ReLU layer, or RMSNorm + rotary + SwiGLU without biases
 
 
 @dataclasses.dataclass(frozen=True)
@@ -38,6 +39,8 @@ class LayerConfig:
     len_hi: int = 0
     config_id: int = 0
     n_layers: int = 1
+    arch: int = CLASSIC
+    rope_base: float = 10000.0    # rotary base (LLAMA layers only)
 
     @property
     def tokens(self) -> int:
@@ -67,14 +70,26 @@ CONFIGS = {
     # 24-layer BERT-large-shaped stack
     "C5": LayerConfig("C5-bert-large-24-layer-bf16", 32, 512, 1024, 16, 4096, causal=0, dropout_p=0.1,
                       dtype=BF16, act=GELU, pre_ln=0, len_lo=128, len_hi=512, config_id=5, n_layers=24),
+    # LLaMA-7B-shaped decoder layer (RMSNorm, rotary, SwiGLU, no biases, no dropout), sequence length of the paper's run
+    "C6": LayerConfig("C6-llama-7b-layer-bf16", 4, 1024, 4096, 32, 11008, causal=1, dropout_p=0.0,
+                      dtype=BF16, pre_ln=1, ln_eps=1e-6, config_id=6, arch=LLAMA),
 }
 
 PARAM_NAMES = ("wqkv", "bqkv", "wo", "bo", "ln1_g", "ln1_b", "w1", "b1", "w2", "b2", "ln2_g", "ln2_b")
 _TENSOR_IDS = {n: i for i, n in enumerate(("x", "dy", "seqlens") + PARAM_NAMES)}
 
 
+LLAMA_PARAM_NAMES = ("wqkv", "wo", "ln1_g", "w1", "w2", "ln2_g")
+
+
+def param_names(cfg: LayerConfig) -> tuple:
+    return LLAMA_PARAM_NAMES if cfg.arch == LLAMA else PARAM_NAMES
+
+
 def param_shapes(cfg: LayerConfig) -> dict:
     H, F = cfg.hidden, cfg.ffn
+    if cfg.arch == LLAMA:   # w1 holds gate (even rows) and up (odd rows) projections
+        return {"wqkv": (3 * H, H), "wo": (H, H), "ln1_g": (H,), "w1": (2 * F, H), "w2": (H, F), "ln2_g": (H,)}
     return {"wqkv": (3 * H, H), "bqkv": (3 * H,), "wo": (H, H), "bo": (H,), "ln1_g": (H,), "ln1_b": (H,),
             "w1": (F, H), "b1": (F,), "w2": (H, F), "b2": (H,), "ln2_g": (H,), "ln2_b": (H,)}
 
