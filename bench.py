@@ -29,7 +29,7 @@ TRAFFIC_BYTES_PER_LAUNCH = {"C2-bert-large-layer-bf16": 108.45e6}   # 100.76 MB 
 def layer_flops(cfg, seqlens):
     """Algorithmic FLOPs of one layer forward+backward: 3 x GEMM + 3.5 x visible attention."""
     T, H, F, S = cfg.tokens, cfg.hidden, cfg.ffn, cfg.seq
-    gemm_fwd = 2.0 * T * (4.0 * H * H + 2.0 * H * F)
+    gemm_fwd = 2.0 * T * (4.0 * H * H + (3.0 if cfg.arch == W.LLAMA else 2.0) * H * F)   # gated FFN: three F x H products
     lens = [S] * cfg.batch if seqlens is None else [int(v) for v in seqlens]
     phi = 0.5 * (1.0 + 1.0 / S) if cfg.causal else 1.0
     att_fwd = sum(4.0 * H * S * l * phi for l in lens)
@@ -50,7 +50,10 @@ def event_time_ms(fn, iters, stream):
 
 def cpu_baseline(cfg, params, x, dy, seqlens):
     """The fp64 oracle, as it stands, on the host cores: one full layer forward+backward."""
-    from oracle import layer as L
+    if cfg.arch == W.LLAMA:
+        from oracle import llama_layer as L
+    else:
+        from oracle import layer as L
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -73,8 +76,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"],
-                    help="C5 = the 24-layer stack (one step = 24 layer forwards, then 24 layer backwards)")
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "C6"],
+                    help="C5 = the 24-layer stack (one step = 24 layer forwards, then 24 layer backwards); "
+                         "C6 = the LLaMA-7B-shaped layer (RMSNorm, rotary, SwiGLU)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--checkpoint", action="store_true",
                     help="activation-checkpointing mode: nothing saved, backward recomputes the forward")
@@ -151,7 +155,9 @@ def main():
     # same tile selection), alone on the launch stream between HIP events.
     tdt = xd.dtype
     mk = lambda *shape: torch.randn(*shape, device="cuda", dtype=torch.float32).to(tdt)
-    tn_shapes = [(H, F, T), (F, H, T), (3 * H, H, T)]          # (M, N, K): C[M,N] = A[K,M]^T B[K,N]
+    llama = cfg.arch == W.LLAMA
+    F1 = 2 * F if llama else F                                  # rows of w1 (gate and up rows interleaved)
+    tn_shapes = [(H, F, T), (F1, H, T), (3 * H, H, T)]         # (M, N, K): C[M,N] = A[K,M]^T B[K,N]
     tn_bufs = [(mk(K, M), mk(K, N), torch.empty(M, N, device="cuda", dtype=tdt)) for (M, N, K) in tn_shapes]
 
     def dominant():
@@ -164,7 +170,8 @@ def main():
     dom_ms = event_time_ms(dominant, reps, stream) / len(tn_shapes)      # average per launch
     dom_flops = sum(2.0 * M * N * K for (M, N, K) in tn_shapes) / len(tn_shapes)
     achieved = dom_flops / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<TN,128,128,64,...> (weight gradients dW2, dW1, dWqkv)",
+    tile = "128,128,64" if cfg.name.startswith("C2") else "..."   # (tile choice depends on the shape; C2's is the profiled one)
+    roofline = {"bound": "mfma", "kernel": f"gemm_bf16_kernel<TN,{tile},...> (weight gradients dW2, dW1, dWqkv)",
                 "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                 "avg_launch_us": dom_ms * 1e3, "flop_per_launch": dom_flops}
@@ -176,19 +183,19 @@ def main():
         torch.cuda.synchronize()
     # for reference: the largest forward GEMM with its fused bias+activation epilogue (FFN1)
     y1 = layer.saved_tensor("n2" if cfg.pre_ln else "y1")
-    try:
-        u = layer.saved_tensor("dact")
-    except Exception:          # a library built before the region was renamed (A/B runs through SLAPO_LIB)
-        u = layer.saved_tensor("u")
-    g = torch.empty_like(u)
+    u = layer.saved_tensor("dgate" if llama else "dact")
+    g = torch.empty(T * F, device="cuda", dtype=tdt)
 
     def ffn1():
-        B.slapo_gemm(dt, B.NT, B.EPI_BIAS_ACT, act, T, F, H, y1, layer.params["w1"], g, bias=layer.params["b1"], aux_out=u)
+        if llama:
+            B.slapo_gemm(dt, B.NT, B.EPI_GATE, act, T, 2 * F, H, y1, layer.params["w1"], g, aux_out=u)
+        else:
+            B.slapo_gemm(dt, B.NT, B.EPI_BIAS_ACT, act, T, F, H, y1, layer.params["w1"], g, bias=layer.params["b1"], aux_out=u)
 
     for _ in range(5):
         ffn1()
     ffn1_ms = event_time_ms(ffn1, reps, stream)
-    ffn1_tf = 2.0 * T * F * H / (ffn1_ms * 1e-3) / 1e12
+    ffn1_tf = 2.0 * T * F1 * H / (ffn1_ms * 1e-3) / 1e12
 
     # the HBM-bound fused epilogue (bias+dropout+residual+LayerNorm forward), algorithmic bytes 4*T*H*eb
     eb = 4 if cfg.dtype == W.FP32 else 2
@@ -199,7 +206,7 @@ def main():
     rstd = torch.empty_like(mu)
 
     def epi():
-        B.slapo_bdrln_fwd(layer.desc, 0, T, r, layer.params["bo"], xd, layer.params["ln1_g"], layer.params["ln1_b"], z, o, mu, rstd)
+        B.slapo_bdrln_fwd(layer.desc, 0, T, r, layer.params.get("bo"), xd, layer.params["ln1_g"], layer.params.get("ln1_b"), z, o, mu, rstd)
 
     r.normal_()
     for _ in range(5):
@@ -226,6 +233,7 @@ def main():
            "config": {"workload": cfg.name, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                       "heads": cfg.heads, "ffn": cfg.ffn, "causal": cfg.causal, "dropout_p": cfg.dropout_p,
                       "attn_dropout_p": cfg.attn_dropout_p, "pre_ln": cfg.pre_ln, "layers": cfg.n_layers, "checkpoint": int(args.checkpoint),
+                      "family": "llama" if llama else "classic",
                       "parallelism": "single-gpu"},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:
@@ -241,9 +249,10 @@ def breakdown(cfg, layer, xd, dyd, sld, stream):
     dev = xd.device
     tdt = xd.dtype
     mk = lambda *s: torch.randn(*s, device=dev, dtype=torch.float32).to(tdt)
-    shapes = [("qkv  NT", B.NT, T, 3 * H, H), ("out  NT", B.NT, T, H, H), ("ffn1 NT", B.NT, T, F, H), ("ffn2 NT", B.NT, T, H, F),
-              ("dG   NN", B.NN, T, F, H), ("dY1  NN", B.NN, T, H, F), ("dA   NN", B.NN, T, H, H), ("dX   NN", B.NN, T, H, 3 * H),
-              ("dW2  TN", B.TN, H, F, T), ("dW1  TN", B.TN, F, H, T), ("dWo  TN", B.TN, H, H, T), ("dWqkv TN", B.TN, 3 * H, H, T)]
+    F1 = 2 * F if cfg.arch == W.LLAMA else F
+    shapes = [("qkv  NT", B.NT, T, 3 * H, H), ("out  NT", B.NT, T, H, H), ("ffn1 NT", B.NT, T, F1, H), ("ffn2 NT", B.NT, T, H, F),
+              ("dG   NN", B.NN, T, F, H), ("dY1  NN", B.NN, T, H, F1), ("dA   NN", B.NN, T, H, H), ("dX   NN", B.NN, T, H, 3 * H),
+              ("dW2  TN", B.TN, H, F, T), ("dW1  TN", B.TN, F1, H, T), ("dWo  TN", B.TN, H, H, T), ("dWqkv TN", B.TN, 3 * H, H, T)]
     tot = 0.0
     for name, layout, M, N, K in shapes:
         a = mk(M, K) if layout != B.TN else mk(K, M)

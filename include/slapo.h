@@ -50,6 +50,13 @@ typedef enum {
 
 enum { SLAPO_BF16 = 0, SLAPO_FP32 = 1, SLAPO_FP16 = 2 };   /* FP16: IEEE half storage, fp32 accumulation, same kernels */
 enum { SLAPO_GELU_ERF = 0, SLAPO_RELU = 1 };
+/* Layer family. CLASSIC: the LayerNorm / bias / GeLU-or-ReLU layer described above (BERT, GPT, OPT ...).
+ * LLAMA: the decoder layer of the LLaMA models the paper also evaluates (section 5.2), i.e. the classic
+ * pre-norm layer with RMSNorm (y = z / sqrt(mean(z^2) + eps) * g) in place of LayerNorm, rotary position
+ * embedding on queries and keys (adjacent pairs (2j, 2j+1) of every head turned by position * base^(-2j/d),
+ * positions counted from 0 in every sequence), a SwiGLU feed-forward block (silu(n Wgate^T) * (n Wup^T)) W2^T
+ * and no bias anywhere. */
+enum { SLAPO_ARCH_CLASSIC = 0, SLAPO_ARCH_LLAMA = 1 };
 
 /* Layer description (host struct). hidden/heads must be 64 or 128; hidden, ffn multiples of 8;
  * hidden <= 4096. */
@@ -75,12 +82,18 @@ typedef struct {
                                dropout(softmax(attn), p) of the attention listing in section 2.2 step 2,
                                applied inside the fused attention kernels (mask stream: site 2, element
                                ((b*heads + a)*seq + i)*seq + j; needs seq % 8 == 0). 0 = none.     */
+  int32_t arch;             /* SLAPO_ARCH_CLASSIC | SLAPO_ARCH_LLAMA (needs pre_ln = 1; act is ignored) */
+  float rope_base;          /* LLAMA: base of the rotary frequencies (10000 in the published models), > 1 */
 } slapo_layer_desc;
 
 /* Parameters: wqkv [3H,H] = [Wq;Wk;Wv] stacked on the output dim, bqkv [3H], wo [H,H], bo [H],
  * ln1_g/ln1_b [H], w1 [F,H], b1 [F], w2 [H,F], b2 [H], ln2_g/ln2_b [H].
  * Post-LN: ln1 follows the attention block, ln2 follows the FFN block.
- * Pre-LN:  ln1 precedes the attention block, ln2 precedes the FFN block. */
+ * Pre-LN:  ln1 precedes the attention block, ln2 precedes the FFN block.
+ * SLAPO_ARCH_LLAMA uses wqkv, wo, ln1_g, w1, w2, ln2_g only (the other entries are ignored and may be NULL;
+ * no gradient is written for them). Its w1 is [2F,H] and holds the gate and up projections interleaved by
+ * rows: row 2c = gate row c, row 2c+1 = up row c, so that one product yields both and a (gate, up) pair
+ * lands in adjacent columns; its gradient has the same layout. */
 typedef struct {
   const void *wqkv, *bqkv, *wo, *bo, *ln1_g, *ln1_b, *w1, *b1, *w2, *b2, *ln2_g, *ln2_b;
 } slapo_layer_params;
@@ -98,7 +111,9 @@ int slapo_layer_workspace(const slapo_layer_desc *desc, size_t *saved_bytes, siz
 /* Named regions inside `saved`, for tests and tools. Writes byte offset and byte length; returns
  * SLAPO_ERR_UNSUPPORTED if the region does not exist for this wiring. Names: "qkv" [T,3H], "attn"
  * [T,H], "lse" [B,heads,S] fp32, "z1" [T,H], "n1" (pre-LN) [T,H], "y1" (post-LN) / "n2" (pre-LN)
- * [T,H], "dact" [T,F] (act'(u) of the FFN pre-activation u), "g" [T,F], "z2" (post-LN) [T,H], "mu1","rstd1","mu2","rstd2" [T] fp32. */
+ * [T,H], "dact" [T,F] (act'(u) of the FFN pre-activation u), "g" [T,F], "z2" (post-LN) [T,H], "mu1","rstd1","mu2","rstd2" [T] fp32.
+ * SLAPO_ARCH_LLAMA: "qkv" holds the rotated queries and keys, "dgate" [T,2F] replaces "dact" (column 2c:
+ * up_c * silu'(gate_c), column 2c+1: silu(gate_c)), "mu1"/"mu2" are unused. */
 int slapo_layer_saved_region(const slapo_layer_desc *desc, const char *name, size_t *offset, size_t *bytes);
 
 /* Forward of the scheduled layer (section 2.2 steps 1-2, appendix schedule):
@@ -106,6 +121,8 @@ int slapo_layer_saved_region(const slapo_layer_desc *desc, const char *name, siz
  *            G = act(Y1 W1^T + b1); Z2 = Y1 + drop1(G W2^T + b2); y = LN2(Z2)
  *   pre-LN:  N1 = LN1(x); QKV from N1; Z1 = x + drop0(A Wo^T + bo); N2 = LN2(Z1);
  *            G = act(N2 W1^T + b1); y = Z1 + drop1(G W2^T + b2)
+ *   LLAMA:   N1 = RMSNorm1(x); QKV = rotate(N1 Wqkv^T); Z1 = x + drop0(A Wo^T); N2 = RMSNorm2(Z1);
+ *            (gate, up) = N2 W1^T; G = silu(gate) * up; y = Z1 + drop1(G W2^T)
  * x, y: [B,S,H]. seqlens: device int32 [B] with 1 <= seqlens[b] <= S (keys j >= seqlens[b] are
  * hidden from every query of sample b), or NULL for no padding mask; may be combined with causal. */
 int slapo_layer_fwd(const slapo_layer_desc *desc, const slapo_layer_params *params, const void *x,
@@ -148,6 +165,10 @@ const char *slapo_status_string(int status);
  *            2: u = acc + bias[n]; C = act(u), aux_out = act'(u)   (F.gelu(bias + x), appendix schedule;
  *               the derivative is all that backward needs of u, and its terms are at hand here)
  *            3: C = acc * aux_in[m,n] (aux_in = the aux_out of epilogue 2)   4: C = acc + aux_in[m,n]  (aux_in may alias C)
+ *            5: columns are (gate, up) pairs (N % 16 == 0): C [M,N/2] = silu(gate) * up,
+ *               aux_out [M,N] = (up * silu'(gate), silu(gate)) per pair            (SwiGLU forward)
+ *            6: C [M,2N] = (acc * aux_in[m,2n], acc * aux_in[m,2n+1]), aux_in [M,2N] = the aux_out of
+ *               epilogue 5: the gradient of the gated values turned into (gate, up) gradient pairs
  * M, N, K > 0; K-contiguous operands need K % 8 == 0, M/N-contiguous ones M % 8 / N % 8 == 0;
  * N % 8 == 0. */
 int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K,
@@ -169,6 +190,8 @@ int slapo_attn_bwd(const slapo_layer_desc *desc, const void *qkv, const int32_t 
 
 /* z = res + keep * (r + bias) / (1 - p)   (bias, dropout, residual; skipped if r == NULL, then z := res)
  * out = LayerNorm(z; gamma, beta), mu/rstd [T] fp32   (skipped if gamma == NULL)
+ * With desc->arch == SLAPO_ARCH_LLAMA the normalisation is RMSNorm (beta and mu are ignored and may be NULL;
+ * rstd = 1/sqrt(mean(z^2) + eps)) and bias may be NULL (= 0); the same holds for slapo_bdrln_bwd (mu ignored).
  * T rows of H elements. z_out may be NULL when only `out` is wanted (r == NULL case).
  * site selects the dropout stream (0 after attention, 1 after the FFN). */
 int slapo_bdrln_fwd(const slapo_layer_desc *desc, int site, int64_t T, const void *r, const void *bias,
@@ -184,6 +207,12 @@ int slapo_bdrln_bwd(const slapo_layer_desc *desc, int site, int64_t T, const voi
                     const float *mu, const float *rstd, const void *gamma, const void *dres_in,
                     void *dz_out, void *dr_out, float *partials, void *stream);
 int slapo_bdrln_bwd_blocks(int64_t T);
+
+/* Rotary embedding (SLAPO_ARCH_LLAMA descriptors only), in place on the Q and K parts of a packed [B,S,3H] array:
+ * pair (2j, 2j+1) of every head at position m is turned by m * rope_base^(-2j/d), by the negative angle if
+ * `inverse` (the transpose, which maps gradients w.r.t. rotated vectors back). table: device scratch of
+ * seq * d/2 * 8 bytes that receives the (cos, sin) pairs. */
+int slapo_rope(const slapo_layer_desc *desc, void *qkv, float *table, int inverse, void *stream);
 
 /* Column sums of a [T,N] matrix in two deterministic stages: partials fp32 [nblk,N] with
  * nblk = slapo_colsum_blocks(T), then slapo_colreduce_partials. */

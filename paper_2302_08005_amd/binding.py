@@ -13,7 +13,8 @@ LIB_PATH = os.environ.get("SLAPO_LIB", os.path.join(HERE, "libslapo_mi355x.so"))
 BF16, FP32, FP16 = 0, 1, 2
 GELU, RELU = 0, 1
 NT, NN, TN = 0, 1, 2
-EPI_NONE, EPI_BIAS, EPI_BIAS_ACT, EPI_DACT, EPI_ADD = 0, 1, 2, 3, 4
+EPI_NONE, EPI_BIAS, EPI_BIAS_ACT, EPI_DACT, EPI_ADD, EPI_GATE, EPI_DGATE = 0, 1, 2, 3, 4, 5, 6
+CLASSIC, LLAMA = 0, 1
 PARAM_NAMES = ("wqkv", "bqkv", "wo", "bo", "ln1_g", "ln1_b", "w1", "b1", "w2", "b2", "ln2_g", "ln2_b")
 
 
@@ -21,7 +22,8 @@ class LayerDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32),
                 ("ffn", C.c_int32), ("causal", C.c_int32), ("dropout_p", C.c_float), ("seed", C.c_uint64),
                 ("dtype", C.c_int32), ("act", C.c_int32), ("pre_ln", C.c_int32), ("layer_id", C.c_int32),
-                ("ln_eps", C.c_float), ("accumulate_grads", C.c_int32), ("checkpoint", C.c_int32), ("attn_dropout_p", C.c_float)]
+                ("ln_eps", C.c_float), ("accumulate_grads", C.c_int32), ("checkpoint", C.c_int32), ("attn_dropout_p", C.c_float),
+                ("arch", C.c_int32), ("rope_base", C.c_float)]
 
 
 class _Ptrs(C.Structure):
@@ -66,6 +68,7 @@ def lib():
             "slapo_colsum_blocks": [i64],
             "slapo_colreduce_partials": [i32, i64, i64, i64, vp, vp, i32, vp],
             "slapo_dropout_mask": [dp, i32, i64, vp, vp],
+            "slapo_rope": [dp, vp, vp, i32, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -101,7 +104,8 @@ def _stream(stream=None):
 def make_desc(cfg=None, **kw) -> LayerDesc:
     """Builds a descriptor from a workloads.LayerConfig-like object and/or keyword overrides."""
     vals = dict(batch=1, seq=1, hidden=64, heads=1, ffn=64, causal=0, dropout_p=0.0, seed=0, dtype=BF16, act=GELU,
-                pre_ln=0, layer_id=0, ln_eps=1e-5, accumulate_grads=0, checkpoint=0, attn_dropout_p=0.0)
+                pre_ln=0, layer_id=0, ln_eps=1e-5, accumulate_grads=0, checkpoint=0, attn_dropout_p=0.0,
+                arch=CLASSIC, rope_base=10000.0)
     if cfg is not None:
         for k in vals:
             if hasattr(cfg, k):
@@ -128,7 +132,7 @@ def slapo_layer_saved_region(desc: LayerDesc, name: str):
 
 
 def _ptr_table(tensors: dict) -> _Ptrs:
-    return _Ptrs(**{n: _p(tensors[n]) for n in PARAM_NAMES})
+    return _Ptrs(**{n: _p(tensors.get(n)) for n in PARAM_NAMES})   # entries a layer family does not have stay NULL
 
 
 def slapo_layer_fwd(desc, params: dict, x, seqlens, y, saved, scratch, stream=None):
@@ -187,6 +191,10 @@ def slapo_colreduce_partials(dtype, nblk, stride, N, partials, out, accumulate=0
 
 def slapo_dropout_mask(desc, site, T, mask, stream=None):
     _check(lib().slapo_dropout_mask(C.byref(desc), site, T, _p(mask), _stream(stream)), "slapo_dropout_mask")
+
+
+def slapo_rope(desc, qkv, table, inverse=0, stream=None):
+    _check(lib().slapo_rope(C.byref(desc), _p(qkv), _p(table), inverse, _stream(stream)), "slapo_rope")
 
 
 def slapo_stack_workspace(desc: LayerDesc, n_layers: int):

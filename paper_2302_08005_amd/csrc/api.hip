@@ -33,6 +33,25 @@ int check_desc(const slapo_layer_desc* d) {
   if (d->attn_dropout_p > 0.f && d->seq % 8 != 0) return SLAPO_ERR_ALIGN;   // a mask block of 8 keys stays inside one query row
   if ((int64_t)d->batch * d->seq * 3 * d->hidden >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->seq * d->ffn >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  if (d->arch != SLAPO_ARCH_CLASSIC && d->arch != SLAPO_ARCH_LLAMA) return SLAPO_ERR_UNSUPPORTED;
+  if (d->arch == SLAPO_ARCH_LLAMA) {
+    if (!d->pre_ln) return SLAPO_ERR_UNSUPPORTED;                    // the family is pre-norm by definition
+    if (!(d->rope_base > 1.f)) return SLAPO_ERR_SHAPE;
+    if ((int64_t)d->batch * d->seq * 2 * d->ffn >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  }
+  return SLAPO_OK;
+}
+
+inline bool is_llama(const slapo_layer_desc* d) { return d->arch == SLAPO_ARCH_LLAMA; }
+// The pointer tables list weight, bias (or gain, offset) alternately; the LLaMA-style layer has the six
+// weights and gains only, i.e. the even entries.
+inline bool param_needed(const slapo_layer_desc* d, int index) { return !is_llama(d) || index % 2 == 0; }
+int check_tables(const slapo_layer_desc* d, const void* const (&ps)[12]) {
+  for (int i = 0; i < 12; ++i) {
+    if (!param_needed(d, i)) continue;
+    if (!ps[i]) return SLAPO_ERR_NULL;
+    if (misaligned(ps[i])) return SLAPO_ERR_ALIGN;
+  }
   return SLAPO_OK;
 }
 
@@ -107,7 +126,7 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
   L.z1 = take(T * H * eb);
   L.n1 = d->pre_ln ? take(T * H * eb) : (size_t)-1;
   L.y1 = take(T * H * eb);  // post-LN: LN1 output; pre-LN: LN2 output ("n2")
-  L.u = take(T * F * eb);
+  L.u = take(T * F * eb * (is_llama(d) ? 2 : 1));   // act'(u), or the (gate, up) factor pairs [T,2F]
   L.g = take(T * F * eb);
   L.z2 = d->pre_ln ? (size_t)-1 : take(T * H * eb);
   L.mu1 = take(T * 4);
@@ -119,7 +138,7 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
 }
 
 struct ScratchLayout {
-  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, acts, total;
+  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, rope, acts, total;
 };
 ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
@@ -131,13 +150,14 @@ ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   L.t1 = take(T * H * eb);
   L.t2 = take(T * H * eb);
   L.t3 = take(T * H * eb);
-  L.du = take(T * F * eb);
+  L.du = take(T * F * eb * (is_llama(d) ? 2 : 1));
   L.dqkv = take(T * 3 * H * eb);
   L.delta = take((size_t)d->batch * d->heads * d->seq * 4);
   L.part_row = take((size_t)bdrln_bwd_blocks((int64_t)T) * 3 * H * 4);
   const size_t widest = F > 3 * H ? F : 3 * H;
   L.part_col = take((size_t)colsum_blocks((int64_t)T) * widest * 4);
   L.part_col2 = take((size_t)colsum_blocks((int64_t)T) * widest * 4);   // the two streams of backward each own one
+  L.rope = is_llama(d) ? take((size_t)d->seq * (d->hidden / d->heads / 2) * 8) : 0;   // (cos, sin) table
   // checkpoint mode: the activations that forward would hand to backward live here instead, for the
   // duration of one call only (backward recomputes them), so the caller keeps nothing per layer but x
   L.acts = d->checkpoint ? take(saved_layout(d).total) : 0;
@@ -186,7 +206,8 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
   else if (!strcmp(name, "n1")) { off = L.n1; len = T * H * eb; }
   else if (!strcmp(name, "y1") && !desc->pre_ln) { off = L.y1; len = T * H * eb; }
   else if (!strcmp(name, "n2") && desc->pre_ln) { off = L.y1; len = T * H * eb; }
-  else if (!strcmp(name, "dact")) { off = L.u; len = T * F * eb; }
+  else if (!strcmp(name, "dact") && !is_llama(desc)) { off = L.u; len = T * F * eb; }
+  else if (!strcmp(name, "dgate") && is_llama(desc)) { off = L.u; len = 2 * T * F * eb; }
   else if (!strcmp(name, "g")) { off = L.g; len = T * F * eb; }
   else if (!strcmp(name, "z2")) { off = L.z2; len = T * H * eb; }
   else if (!strcmp(name, "mu1")) { off = L.mu1; len = T * 4; }
@@ -216,24 +237,39 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   const AttnShape as = make_attn_shape(d);
   const DropoutParams dp0 = make_dropout(d, 0), dp1 = make_dropout(d, 1);
 
+  const bool llama = is_llama(d);
+  const int rms = llama ? 1 : 0;
   const void* attn_in = x;
   if (d->pre_ln) {
     void* n1 = sv + L.n1;
-    launch_bdrln_fwd(dt, T, H, nullptr, nullptr, x, p->ln1_g, p->ln1_b, nullptr, n1, mu1, rstd1, dp0, d->ln_eps, st);
+    launch_bdrln_fwd(dt, T, H, nullptr, nullptr, x, p->ln1_g, p->ln1_b, nullptr, n1, mu1, rstd1, dp0, d->ln_eps, rms, st);
     attn_in = n1;
   }
-  launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
+  if (llama) {
+    // no biases; queries and keys are rotated in place by their position before the attention reads them
+    float* table = (float*)(sc + W.rope);
+    launch_rope_table(d->seq, H / d->heads, d->rope_base, table, st);
+    launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, nullptr, nullptr, nullptr, st);
+    launch_rope(dt, T, d->seq, H, H / d->heads, table, qkv, 0, st);
+  } else {
+    launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
+  }
   launch_attn_fwd(dt, as, qkv, seqlens, attn, lse, st);
   launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, H, attn, p->wo, r, nullptr, nullptr, nullptr, st);
-  if (d->pre_ln) launch_bdrln_fwd(dt, T, H, r, p->bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, st);
-  else launch_bdrln_fwd(dt, T, H, r, p->bo, x, p->ln1_g, p->ln1_b, z1, y1, mu1, rstd1, dp0, d->ln_eps, st);
-  launch_gemm(dt, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st);
+  const void* bo = llama ? nullptr : p->bo;
+  const void* b2 = llama ? nullptr : p->b2;
+  if (d->pre_ln) launch_bdrln_fwd(dt, T, H, r, bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, rms, st);
+  else launch_bdrln_fwd(dt, T, H, r, bo, x, p->ln1_g, p->ln1_b, z1, y1, mu1, rstd1, dp0, d->ln_eps, rms, st);
+  if (llama)   // w1 holds (gate, up) row pairs: one product, gated in the epilogue; `u` keeps the backward factors
+    launch_gemm(dt, GEMM_NT, EPI_GATE, d->act, T, 2 * F, H, y1, p->w1, g, nullptr, nullptr, u, st);
+  else
+    launch_gemm(dt, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st);
   launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st);
   if (d->pre_ln) {
-    launch_bdrln_fwd(dt, T, H, r, p->b2, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, dp1, d->ln_eps, st);
+    launch_bdrln_fwd(dt, T, H, r, b2, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, dp1, d->ln_eps, rms, st);
   } else {
     void* z2 = sv + L.z2;
-    launch_bdrln_fwd(dt, T, H, r, p->b2, y1, p->ln2_g, p->ln2_b, z2, y, mu2, rstd2, dp1, d->ln_eps, st);
+    launch_bdrln_fwd(dt, T, H, r, b2, y1, p->ln2_g, p->ln2_b, z2, y, mu2, rstd2, dp1, d->ln_eps, rms, st);
   }
 }
 
@@ -242,8 +278,8 @@ int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   int rc = check_desc(d);
   if (rc) return rc;
   if (!p || !x || !y || !scratch || (!saved && !d->checkpoint)) return SLAPO_ERR_NULL;
-  const void* ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
-  for (const void* q : ps) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
+  const void* const ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
+  if ((rc = check_tables(d, ps))) return rc;
   if (misaligned(x) || misaligned(y) || misaligned(scratch) || (!d->checkpoint && misaligned(saved))) return SLAPO_ERR_ALIGN;
   if (d->checkpoint) saved = (char*)scratch + scratch_layout(d).acts;   // transient: nothing is kept for backward
   run_forward(d, p, x, seqlens, y, saved, scratch, (hipStream_t)stream);
@@ -256,10 +292,9 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   int rc = check_desc(d);
   if (rc) return rc;
   if (!p || !x || !dy || !dx || !gr || !scratch || (!saved && !d->checkpoint)) return SLAPO_ERR_NULL;
-  const void* ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
-  const void* gs[12] = {gr->wqkv, gr->bqkv, gr->wo, gr->bo, gr->ln1_g, gr->ln1_b, gr->w1, gr->b1, gr->w2, gr->b2, gr->ln2_g, gr->ln2_b};
-  for (const void* q : ps) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
-  for (const void* q : gs) { if (!q) return SLAPO_ERR_NULL; if (misaligned(q)) return SLAPO_ERR_ALIGN; }
+  const void* const ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
+  const void* const gs[12] = {gr->wqkv, gr->bqkv, gr->wo, gr->bo, gr->ln1_g, gr->ln1_b, gr->w1, gr->b1, gr->w2, gr->b2, gr->ln2_g, gr->ln2_b};
+  if ((rc = check_tables(d, ps)) || (rc = check_tables(d, gs))) return rc;
   if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(scratch) || (!d->checkpoint && misaligned(saved))) return SLAPO_ERR_ALIGN;
 
   hipStream_t st = (hipStream_t)stream;
@@ -306,47 +341,67 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   };
   // Buffers: t0 dZ2 -> dY1/dN2 -> dA -> dN1; t1 dR2 (kept for dW2); t2 dZ1; t3 dR1 (kept for dWo).
 
+  const bool llama = is_llama(d);
+  const int rms = llama ? 1 : 0;
+  // the LLaMA-style layer has no bias or offset gradients: those outputs are simply not produced
+  void *g_b2 = llama ? nullptr : gr->b2, *g_bo = llama ? nullptr : gr->bo;
+  void *g_ln1_b = llama ? nullptr : gr->ln1_b, *g_ln2_b = llama ? nullptr : gr->ln2_b;
+
   // ---- FFN block ----
   if (d->pre_ln) {
-    launch_bdrln_bwd(dt, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, st);
-    reduce_rows(nullptr, nullptr, gr->b2);
+    launch_bdrln_bwd(dt, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, rms, st);
+    if (!llama) reduce_rows(nullptr, nullptr, g_b2);
   } else {
-    launch_bdrln_bwd(dt, T, H, dy, sv + L.z2, mu2, rstd2, p->ln2_g, nullptr, t0, t1, prow, dp1, st);
-    reduce_rows(gr->ln2_g, gr->ln2_b, gr->b2);
+    launch_bdrln_bwd(dt, T, H, dy, sv + L.z2, mu2, rstd2, p->ln2_g, nullptr, t0, t1, prow, dp1, rms, st);
+    reduce_rows(gr->ln2_g, g_ln2_b, g_b2);
   }
   fork(0);
   dweight(H, F, t1, g, gr->w2);
-  launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
-  fork(1);
-  colsum(du, F, gr->b1, ws);
-  dweight(F, H, du, y1, gr->w1);
-  if (d->pre_ln) launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
-  else launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
+  if (llama) {
+    // dG = dR2 W2, turned into the (gate, up) gradient pairs [T,2F] by the two saved factors in the epilogue
+    launch_gemm(dt, GEMM_NN, EPI_DGATE, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+    fork(1);
+    dweight(2 * F, H, du, y1, gr->w1);
+    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 2 * F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
+  } else {
+    launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+    fork(1);
+    colsum(du, F, gr->b1, ws);
+    dweight(F, H, du, y1, gr->w1);
+    if (d->pre_ln) launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
+    else launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
+  }
   // ---- attention block ----
   if (d->pre_ln) {
-    launch_bdrln_bwd(dt, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t3, prow, dp0, st);
-    reduce_rows(gr->ln2_g, gr->ln2_b, gr->bo);
+    launch_bdrln_bwd(dt, T, H, t0, z1, mu2, rstd2, p->ln2_g, dy, t2, t3, prow, dp0, rms, st);
+    reduce_rows(gr->ln2_g, g_ln2_b, g_bo);
   } else {
-    launch_bdrln_bwd(dt, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t3, prow, dp0, st);
-    reduce_rows(gr->ln1_g, gr->ln1_b, gr->bo);
+    launch_bdrln_bwd(dt, T, H, t0, z1, mu1, rstd1, p->ln1_g, nullptr, t2, t3, prow, dp0, rms, st);
+    reduce_rows(gr->ln1_g, g_ln1_b, g_bo);
   }
   fork(2);
   dweight(H, H, t3, attn, gr->wo);
   launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
   launch_attn_bwd(dt, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
+  if (llama) {
+    // the attention gradients are w.r.t. the rotated queries and keys: turn them back (the rotation's transpose)
+    float* table = (float*)(sc + W.rope);
+    if (!d->checkpoint) launch_rope_table(d->seq, H / d->heads, d->rope_base, table, st);   // else the recomputed forward just wrote it
+    launch_rope(dt, T, d->seq, H, H / d->heads, table, dqkv, 1, st);
+  }
   fork(3);
   if (d->pre_ln) {
     dweight(3 * H, H, dqkv, sv + L.n1, gr->wqkv);
     launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * H, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
-    launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, st);
-    reduce_rows(gr->ln1_g, gr->ln1_b, nullptr);
+    launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, rms, st);
+    reduce_rows(gr->ln1_g, g_ln1_b, nullptr);
   } else {
     dweight(3 * H, H, dqkv, x, gr->wqkv);
     launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
   }
   // the last bias gradient goes behind the data gradient on the caller's stream: the helper stream's last
   // product is the longer one, and this way the two streams end at about the same time
-  colsum(dqkv, 3 * H, gr->bqkv, st);
+  if (!llama) colsum(dqkv, 3 * H, gr->bqkv, st);
   if (side) {   // join: the caller's stream continues only after the weight gradients are complete
     (void)hipEventRecord(side->join, ws);
     (void)hipStreamWaitEvent(st, side->join, 0);
@@ -416,15 +471,16 @@ int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
 int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
                const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
   if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
-  if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_ADD) return SLAPO_ERR_UNSUPPORTED;
+  if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_DGATE) return SLAPO_ERR_UNSUPPORTED;
   if (act != SLAPO_GELU_ERF && act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
   if (M <= 0 || N <= 0 || K <= 0) return SLAPO_ERR_SHAPE;
   if (M * N >= ((int64_t)1 << 31) || M * K >= ((int64_t)1 << 31) || N * K >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if (!A || !B || !C) return SLAPO_ERR_NULL;
   if ((epilogue == EPI_BIAS || epilogue == EPI_BIAS_ACT) && !bias) return SLAPO_ERR_NULL;
-  if (epilogue == EPI_BIAS_ACT && !aux_out) return SLAPO_ERR_NULL;
-  if ((epilogue == EPI_DACT || epilogue == EPI_ADD) && !aux_in) return SLAPO_ERR_NULL;
-  if (N % 8) return SLAPO_ERR_ALIGN;
+  if ((epilogue == EPI_BIAS_ACT || epilogue == EPI_GATE) && !aux_out) return SLAPO_ERR_NULL;
+  if ((epilogue == EPI_DACT || epilogue == EPI_ADD || epilogue == EPI_DGATE) && !aux_in) return SLAPO_ERR_NULL;
+  if (epilogue == EPI_DGATE && 2 * M * N >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  if (N % 8 || (epilogue == EPI_GATE && N % 16)) return SLAPO_ERR_ALIGN;
   if (layout == GEMM_TN ? (M % 8) : (K % 8)) return SLAPO_ERR_ALIGN;   // A's contiguous dimension
   if (layout == GEMM_NT && (K % 8)) return SLAPO_ERR_ALIGN;
   if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
@@ -461,14 +517,15 @@ int slapo_bdrln_fwd(const slapo_layer_desc* d, int site, int64_t T, const void* 
   const int rc = check_desc(d);
   if (rc) return rc;
   if (T <= 0 || site < 0 || site > 1) return SLAPO_ERR_SHAPE;
+  const bool llama = is_llama(d);   // RMSNorm: no offset, no mean; no biases
   if (!res) return SLAPO_ERR_NULL;
-  if (r && (!bias || !z_out)) return SLAPO_ERR_NULL;
-  if (gamma && (!beta || !out || !mu || !rstd)) return SLAPO_ERR_NULL;
+  if (r && ((!bias && !llama) || !z_out)) return SLAPO_ERR_NULL;
+  if (gamma && (!out || !rstd || (!llama && (!beta || !mu)))) return SLAPO_ERR_NULL;
   if (!r && !gamma) return SLAPO_ERR_NULL;
   if (misaligned(r) || misaligned(bias) || misaligned(res) || misaligned(gamma) || misaligned(beta) ||
       misaligned(z_out) || misaligned(out)) return SLAPO_ERR_ALIGN;
   launch_bdrln_fwd(d->dtype, T, d->hidden, r, bias, res, gamma, beta, z_out, out, mu, rstd,
-                   make_dropout(d, site), d->ln_eps, (hipStream_t)stream);
+                   make_dropout(d, site), d->ln_eps, llama ? 1 : 0, (hipStream_t)stream);
   return finish();
 }
 
@@ -481,12 +538,24 @@ int slapo_bdrln_bwd(const slapo_layer_desc* d, int site, int64_t T, const void* 
   if (rc) return rc;
   if (T <= 0 || site < 0 || site > 1) return SLAPO_ERR_SHAPE;
   if (!dout || !partials) return SLAPO_ERR_NULL;
-  if (gamma && (!z || !mu || !rstd)) return SLAPO_ERR_NULL;
+  if (gamma && (!z || !rstd || (!mu && !is_llama(d)))) return SLAPO_ERR_NULL;
   if (!dz_out && !dr_out) return SLAPO_ERR_NULL;
   if (misaligned(dout) || misaligned(z) || misaligned(gamma) || misaligned(dres_in) || misaligned(dz_out) ||
       misaligned(dr_out) || misaligned(partials)) return SLAPO_ERR_ALIGN;
   launch_bdrln_bwd(d->dtype, T, d->hidden, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials,
-                   make_dropout(d, site), (hipStream_t)stream);
+                   make_dropout(d, site), is_llama(d) ? 1 : 0, (hipStream_t)stream);
+  return finish();
+}
+
+int slapo_rope(const slapo_layer_desc* d, void* qkv, float* table, int inverse, void* stream) {
+  const int rc = check_desc(d);
+  if (rc) return rc;
+  if (!is_llama(d)) return SLAPO_ERR_UNSUPPORTED;
+  if (!qkv || !table) return SLAPO_ERR_NULL;
+  if (misaligned(qkv) || misaligned(table)) return SLAPO_ERR_ALIGN;
+  const int hd = d->hidden / d->heads;
+  launch_rope_table(d->seq, hd, d->rope_base, table, (hipStream_t)stream);
+  launch_rope(d->dtype, (int64_t)d->batch * d->seq, d->seq, d->hidden, hd, table, qkv, inverse ? 1 : 0, (hipStream_t)stream);
   return finish();
 }
 

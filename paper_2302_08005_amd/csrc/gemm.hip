@@ -69,6 +69,20 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
   from_f32(C[idx], v);
 }
 
+// silu(u) = u * sigmoid(u) and the two factors the gated feed-forward block keeps for backward
+struct GateTerms { float out, dgate, dup; };   // silu(u) * w, w * silu'(u), silu(u)
+template <bool FAST>
+__device__ __forceinline__ GateTerms gate_terms(float u, float w) {
+  const float sg = FAST ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u * -1.4426950408889634f))
+                        : 1.0f / (1.0f + expf(-u));
+  const float s = u * sg;
+  GateTerms g;
+  g.out = s * w;
+  g.dgate = w * (sg + s * (1.0f - sg));   // silu'(u) = sigmoid(u) (1 + u (1 - sigmoid(u)))
+  g.dup = s;
+  return g;
+}
+
 // LDS layouts. Every tile sits in LDS unpadded and in memory order, 16 bytes of thread t of a slab at byte
 // 16 t of the stage, so that a slab can be brought in either through registers or by the direct
 // global -> LDS loads of gfx950 (one wave-level load fills 1 KB of consecutive LDS, lane l at byte 16 l).
@@ -449,16 +463,23 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   if ((EPI == EPI_BIAS || EPI == EPI_BIAS_ACT) && n < N) load8h<F16>(bias + n, bv);
   // The auxiliary input of a 32-row slab is fetched one slab ahead (clamped addresses, so the loads are
   // unconditional): its latency passes while the slab before it is staged and written out.
-  constexpr bool AUX = (EPI == EPI_DACT || EPI == EPI_ADD);
+  constexpr bool AUX = (EPI == EPI_DACT || EPI == EPI_ADD || EPI == EPI_DGATE);
   constexpr int NP = 32 / RPP;
-  u32x4_t au[TM][NP];
-  auto aux_fetch = [&](int i, u32x4_t (&dst)[NP]) {
+  constexpr int NAUX = EPI == EPI_DGATE ? 2 : 1;   // 16-byte pieces of auxiliary input per 8 product columns
+  u32x4_t au[TM][NP * NAUX];
+  auto aux_fetch = [&](int i, u32x4_t (&dst)[NP * NAUX]) {
     const int nc = n < N ? n : N - 8;
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass) {
       int m = m0 + wm0 + i * 32 + pass * RPP + rr;
       m = m < M ? m : M - 1;
-      dst[pass] = *reinterpret_cast<const u32x4_t*>(aux_in + (int64_t)m * N + nc);
+      if constexpr (EPI == EPI_DGATE) {   // the factor pairs of product columns nc..nc+7 sit in columns 2nc..2nc+15 of [M,2N]
+        const bf16_t* q = aux_in + (int64_t)m * (2 * N) + 2 * nc;
+        dst[2 * pass] = *reinterpret_cast<const u32x4_t*>(q);
+        dst[2 * pass + NAUX - 1] = *reinterpret_cast<const u32x4_t*>(q + 8);
+      } else {
+        dst[pass] = *reinterpret_cast<const u32x4_t*>(aux_in + (int64_t)m * N + nc);
+      }
     }
   };
   auto aux_get = [](const u32x4_t& w, float (&u)[8]) {
@@ -517,8 +538,33 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
           aux_get(au[i][pass], u);
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += u[e];
+        } else if (EPI == EPI_GATE) {
+          // columns come as (gate, up) pairs: four gated values go to C [M,N/2], the backward factors stay [M,N]
+          float f[8], o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const GateTerms g = gate_terms<true>(v[2 * e], v[2 * e + 1]);
+            o[e] = g.out; f[2 * e] = g.dgate; f[2 * e + 1] = g.dup;
+          }
+          store8h<F16>(aux_out + idx, f);
+          uint2 w;
+          w.x = pack2<F16>(o[0], o[1]);
+          w.y = pack2<F16>(o[2], o[3]);
+          *reinterpret_cast<uint2*>(C + (int64_t)m * (N / 2) + n / 2) = w;
+        } else if constexpr (EPI == EPI_DGATE) {
+          float fa[8], fb[8], o0[8], o1[8];
+          aux_get(au[i][2 * pass], fa);
+          aux_get(au[i][2 * pass + NAUX - 1], fb);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            o0[2 * e] = v[e] * fa[2 * e]; o0[2 * e + 1] = v[e] * fa[2 * e + 1];
+            o1[2 * e] = v[4 + e] * fb[2 * e]; o1[2 * e + 1] = v[4 + e] * fb[2 * e + 1];
+          }
+          bf16_t* q = C + (int64_t)m * (2 * N) + 2 * n;
+          store8h<F16>(q, o0);
+          store8h<F16>(q + 8, o1);
         }
-        store8h<F16>(C + idx, v);
+        if (EPI != EPI_GATE && EPI != EPI_DGATE) store8h<F16>(C + idx, v);
       }
     }
   }
@@ -573,14 +619,27 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, cons
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-      if (m < M && n < N) epilogue_store<float>(epi, act, acc[i][j], m, n, N, C, bias, aux_in, aux_out);
+      if (m >= M || n >= N) continue;
+      if (epi == EPI_GATE) {          // (gate, up) pairs in adjacent columns; the even one does the work
+        if (j & 1) continue;
+        const GateTerms g = gate_terms<false>(acc[i][j], acc[i][j + 1]);
+        C[(int64_t)m * (N / 2) + n / 2] = g.out;
+        aux_out[(int64_t)m * N + n] = g.dgate;
+        aux_out[(int64_t)m * N + n + 1] = g.dup;
+      } else if (epi == EPI_DGATE) {
+        const int64_t q = (int64_t)m * (2 * N) + 2 * n;
+        C[q] = acc[i][j] * aux_in[q];
+        C[q + 1] = acc[i][j] * aux_in[q + 1];
+      } else {
+        epilogue_store<float>(epi, act, acc[i][j], m, n, N, C, bias, aux_in, aux_out);
+      }
     }
 }
 
 // epilogue / layout pairs the layer itself uses; only these get the tuned (deep-prefetch) kernels
 constexpr bool epi_used(int layout, int epi) {
-  return layout == GEMM_NT ? (epi == EPI_NONE || epi == EPI_BIAS || epi == EPI_BIAS_ACT)
-       : layout == GEMM_NN ? (epi == EPI_NONE || epi == EPI_DACT || epi == EPI_ADD)
+  return layout == GEMM_NT ? (epi == EPI_NONE || epi == EPI_BIAS || epi == EPI_BIAS_ACT || epi == EPI_GATE)
+       : layout == GEMM_NN ? (epi == EPI_NONE || epi == EPI_DACT || epi == EPI_ADD || epi == EPI_DGATE)
                            : (epi == EPI_NONE || epi == EPI_ADD);
 }
 
@@ -607,6 +666,8 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
     case EPI_BIAS: SLAPO_GEMM(EPI_BIAS); break;
     case EPI_BIAS_ACT: SLAPO_GEMM(EPI_BIAS_ACT); break;
     case EPI_DACT: SLAPO_GEMM(EPI_DACT); break;
+    case EPI_GATE: SLAPO_GEMM(EPI_GATE); break;
+    case EPI_DGATE: SLAPO_GEMM(EPI_DGATE); break;
     default: SLAPO_GEMM(EPI_ADD); break;
   }
 #undef SLAPO_GEMM

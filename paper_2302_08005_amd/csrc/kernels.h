@@ -7,7 +7,10 @@
 namespace slapo {
 
 enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
-enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_ACT = 2, EPI_DACT = 3, EPI_ADD = 4 };
+// EPI_GATE: the product's columns are (gate, up) pairs; C [M,N/2] = silu(gate) * up, aux_out [M,N] = the pair
+//   (up * silu'(gate), silu(gate)), the two factors backward multiplies the gradient of C with.
+// EPI_DGATE: the product is that gradient [M,N]; C [M,2N] = (acc * aux_in[m,2n], acc * aux_in[m,2n+1]).
+enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_ACT = 2, EPI_DACT = 3, EPI_ADD = 4, EPI_GATE = 5, EPI_DGATE = 6 };
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
                  void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st);
@@ -22,13 +25,21 @@ void launch_attn_fwd(int dtype, const AttnShape& s, const void* qkv, const int32
 void launch_attn_bwd(int dtype, const AttnShape& s, const void* qkv, const int32_t* seqlens, const void* out,
                      const void* dout, const float* lse, float* delta, void* dqkv, hipStream_t st);
 
+// rms: the normalisation is RMSNorm (no mean subtraction, no offset; beta, mu unused). bias may be null.
 void launch_bdrln_fwd(int dtype, int64_t rows, int H, const void* r, const void* bias, const void* res,
                       const void* gamma, const void* beta, void* z_out, void* out, float* mu, float* rstd,
-                      const DropoutParams& dp, float eps, hipStream_t st);
+                      const DropoutParams& dp, float eps, int rms, hipStream_t st);
 int bdrln_bwd_blocks(int64_t rows);
 void launch_bdrln_bwd(int dtype, int64_t rows, int H, const void* dout, const void* z, const float* mu,
                       const float* rstd, const void* gamma, const void* dres_in, void* dz_out, void* dr_out,
-                      float* partials, const DropoutParams& dp, hipStream_t st);
+                      float* partials, const DropoutParams& dp, int rms, hipStream_t st);
+// Rotary embedding on the Q and K parts of a packed [rows, 3H] array, in place: inside every head of width d
+// the adjacent pair (2j, 2j+1) of row t is turned by the angle of table entry (t % seq, j) (negated when
+// `inverse`). table: [seq, d/2] (cos, sin) pairs in fp32, written by launch_rope_table (angle m * base^(-2j/d),
+// evaluated in double precision).
+void launch_rope_table(int seq, int d, float base, float* table, hipStream_t st);
+void launch_rope(int dtype, int64_t rows, int seq, int H, int d, const float* table, void* qkv, int inverse,
+                 hipStream_t st);
 int colsum_blocks(int64_t rows);
 void launch_colsum_partials(int dtype, int64_t rows, int64_t N, const void* a, float* partials,
                             hipStream_t st);

@@ -15,7 +15,7 @@ template <typename T, int NCH, bool BDR, bool LN, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void bdrln_fwd_kernel(
     int64_t rows, int H, const T* __restrict__ r, const T* __restrict__ bias, const T* __restrict__ res,
     const T* __restrict__ gamma, const T* __restrict__ beta, T* __restrict__ z_out, T* __restrict__ out,
-    float* __restrict__ mu_out, float* __restrict__ rstd_out, DropoutParams dp, float eps) {
+    float* __restrict__ mu_out, float* __restrict__ rstd_out, DropoutParams dp, float eps, int rms) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nchunk = H >> 3;
   const float inv_h = 1.0f / (float)H;
@@ -29,9 +29,9 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_fwd_kernel(
       if (c < nchunk) {
         load8(res + base + c * 8, v[i]);
         if (BDR) {
-          float a[8], b[8];
+          float a[8], b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           load8(r + base + c * 8, a);
-          load8(bias + c * 8, b);
+          if (bias) load8(bias + c * 8, b);
           const uint32_t keep = dropout_keep8(dp, (uint64_t)(base >> 3) + (uint64_t)c);
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_fwd_kernel(
       }
     }
     if (!LN) continue;
-    const float mean = wave_sum(sum) * inv_h;
+    const float mean = rms ? 0.f : wave_sum(sum) * inv_h;   // RMSNorm: second moment about zero
     float sq = 0.f;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
@@ -62,14 +62,14 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_fwd_kernel(
       }
     }
     const float rstd = rsqrtf(wave_sum(sq) * inv_h + eps);
-    if (lane == 0) { mu_out[row] = mean; rstd_out[row] = rstd; }
+    if (lane == 0) { if (mu_out) mu_out[row] = mean; rstd_out[row] = rstd; }
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = lane + 64 * i;
       if (c < nchunk) {
-        float g[8], b[8], y[8];
+        float g[8], b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, y[8];
         load8(gamma + c * 8, g);
-        load8(beta + c * 8, b);
+        if (beta) load8(beta + c * 8, b);
 #pragma unroll
         for (int j = 0; j < 8; ++j) y[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
         store8(out + base + c * 8, y);
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
         if (dres_in) nres[i].load(dres_in + base + c * 8);
       }
     }
-    if (LN) { nm = mu[r]; nrs = rstd[r]; }
+    if (LN) { nm = mu ? mu[r] : 0.f; nrs = rstd[r]; }   // no mu: RMSNorm
   };
   // (issuing the next row's loads ahead of the reductions was measured and made no difference)
   for (int64_t row = (int64_t)blockIdx.x * WAVES + wave; row < rows; row += stride) {
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
         }
       }
     }
-    if (LN) { s1 = wave_sum(s1) * inv_h; s2 = wave_sum(s2) * inv_h; }
+    if (LN) { s1 = mu ? wave_sum(s1) * inv_h : 0.f; s2 = wave_sum(s2) * inv_h; }
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = lane + 64 * i;
@@ -302,14 +302,14 @@ static int nch_for(int H) { const int n = (H / 8 + 63) / 64; return n <= 1 ? 1 :
 template <typename T, bool BDR, bool LN>
 static void launch_fwd(int64_t rows, int H, const void* r, const void* bias, const void* res, const void* gamma,
                        const void* beta, void* z_out, void* out, float* mu, float* rstd, const DropoutParams& dp,
-                       float eps, hipStream_t st) {
+                       float eps, int rms, hipStream_t st) {
   constexpr int WAVES = 4;
   int64_t blocks = (rows + WAVES - 1) / WAVES;
   if (blocks > 4096) blocks = 4096;
 #define SLAPO_FWD(N)                                                                                          \
   hipLaunchKernelGGL((bdrln_fwd_kernel<T, N, BDR, LN, WAVES>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, st, \
                      rows, H, (const T*)r, (const T*)bias, (const T*)res, (const T*)gamma, (const T*)beta,    \
-                     (T*)z_out, (T*)out, mu, rstd, dp, eps)
+                     (T*)z_out, (T*)out, mu, rstd, dp, eps, rms)
   switch (nch_for(H)) {
     case 1: SLAPO_FWD(1); break;
     case 2: SLAPO_FWD(2); break;
@@ -322,12 +322,13 @@ static void launch_fwd(int64_t rows, int H, const void* r, const void* bias, con
 
 void launch_bdrln_fwd(int dtype, int64_t rows, int H, const void* r, const void* bias, const void* res,
                       const void* gamma, const void* beta, void* z_out, void* out, float* mu, float* rstd,
-                      const DropoutParams& dp, float eps, hipStream_t st) {
+                      const DropoutParams& dp, float eps, int rms, hipStream_t st) {
   const bool bdr = r != nullptr, ln = gamma != nullptr;
+  if (rms) { beta = nullptr; mu = nullptr; }
 #define SLAPO_PICK(T)                                                                                   \
-  if (bdr && ln) launch_fwd<T, true, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st); \
-  else if (bdr) launch_fwd<T, true, false>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st); \
-  else launch_fwd<T, false, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, st)
+  if (bdr && ln) launch_fwd<T, true, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, rms, st); \
+  else if (bdr) launch_fwd<T, true, false>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, rms, st); \
+  else launch_fwd<T, false, true>(rows, H, r, bias, res, gamma, beta, z_out, out, mu, rstd, dp, eps, rms, st)
   if (dtype == DT_FP32) { SLAPO_PICK(float); } else if (dtype == DT_FP16) { SLAPO_PICK(f16_t); } else { SLAPO_PICK(bf16_t); }
 #undef SLAPO_PICK
 }
@@ -362,7 +363,8 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
 
 void launch_bdrln_bwd(int dtype, int64_t rows, int H, const void* dout, const void* z, const float* mu,
                       const float* rstd, const void* gamma, const void* dres_in, void* dz_out, void* dr_out,
-                      float* partials, const DropoutParams& dp, hipStream_t st) {
+                      float* partials, const DropoutParams& dp, int rms, hipStream_t st) {
+  if (rms) mu = nullptr;   // the kernel reads a missing mean as RMSNorm (mean 0, no mean-of-gradient term)
   const bool ln = gamma != nullptr;
 #define SLAPO_PICK(T)                                                                                          \
   if (ln) launch_bwd<T, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);     \
@@ -439,6 +441,61 @@ void launch_colreduce3(int dtype, int64_t nblk, int H, const float* partials, vo
 void launch_dropout_mask(int64_t n_elements, uint8_t* mask, const DropoutParams& dp, hipStream_t st) {
   const int64_t nb = n_elements / 8;
   hipLaunchKernelGGL(dropout_mask_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, nb, mask, dp);
+}
+
+// ---- rotary position embedding ---------------------------------------------------------------------
+// (cos, sin) of position m, pair j, for the angle m * base^(-j / half) (= m * base^(-2j/d)). Evaluated in
+// double precision: positions reach thousands of radians, where an fp32 angle alone would cost 1e-4.
+__global__ __launch_bounds__(256) void rope_table_kernel(int seq, int half, double log_base, float2* __restrict__ table) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= seq * half) return;
+  const int m = idx / half, j = idx % half;
+  const double angle = (double)m * exp(-log_base * (double)j / (double)half);
+  double sn, cs;
+  sincos(angle, &sn, &cs);
+  table[idx] = make_float2((float)cs, (float)sn);
+}
+
+// One thread turns the four adjacent pairs of 8 consecutive columns of the Q or K part of one row, in place.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(int64_t rows, int seq, int H, int d, const float2* __restrict__ table,
+                                                   T* qkv, int inverse) {
+  const int64_t per_row = (2 * (int64_t)H) >> 3;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * per_row) return;
+  const int64_t t = idx / per_row;
+  const int n = (int)(idx - t * per_row) * 8;
+  const int pos = (int)(t % seq), half = d >> 1;
+  const float4* tb = reinterpret_cast<const float4*>(table + (int64_t)pos * half + ((n % d) >> 1));
+  const float4 t0 = tb[0], t1 = tb[1];
+  const float cs[4] = {t0.x, t0.z, t1.x, t1.z};
+  const float sn[4] = {t0.y, t0.w, t1.y, t1.w};
+  T* p = qkv + t * 3 * H + n;
+  float v[8];
+  load8(p, v);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float s = inverse ? -sn[e] : sn[e], a = v[2 * e], b = v[2 * e + 1];
+    v[2 * e] = a * cs[e] - b * s;
+    v[2 * e + 1] = a * s + b * cs[e];
+  }
+  store8(p, v);
+}
+
+void launch_rope_table(int seq, int d, float base, float* table, hipStream_t st) {
+  const int n = seq * (d / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, seq, d / 2,
+                     log((double)base), reinterpret_cast<float2*>(table));
+}
+
+void launch_rope(int dtype, int64_t rows, int seq, int H, int d, const float* table, void* qkv, int inverse,
+                 hipStream_t st) {
+  const int64_t n = rows * (2 * (int64_t)H / 8);
+  const dim3 grid((unsigned)((n + 255) / 256));
+  const float2* tb = reinterpret_cast<const float2*>(table);
+  if (dtype == DT_FP32) hipLaunchKernelGGL(rope_kernel<float>, grid, dim3(256), 0, st, rows, seq, H, d, tb, (float*)qkv, inverse);
+  else if (dtype == DT_FP16) hipLaunchKernelGGL(rope_kernel<f16_t>, grid, dim3(256), 0, st, rows, seq, H, d, tb, (f16_t*)qkv, inverse);
+  else hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, dim3(256), 0, st, rows, seq, H, d, tb, (bf16_t*)qkv, inverse);
 }
 
 }  // namespace slapo
