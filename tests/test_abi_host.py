@@ -55,7 +55,7 @@ def test_null_and_alignment_errors_come_before_any_device_work():
     assert lib.slapo_gemm(0, 0, 0, 0, 128, 128, 0, 4096, 4096, 4096, None, None, None, None) == -2
     assert lib.slapo_gemm(0, 0, 1, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -1
     assert lib.slapo_gemm(0, 0, 0, 0, 128, 132, 64, 4096, 4096, 4096, None, None, None, None) == -4
-    assert lib.slapo_gemm(0, 5, 0, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -3
+    assert lib.slapo_gemm(0, 5, 0, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -3   # unknown layout
     assert lib.slapo_dropout_mask(C.byref(d), 2, 256, 4096, None) == -2
     assert B.status_string(-6).startswith("HIP")
 
@@ -91,3 +91,36 @@ def test_stack_workspace_and_argument_checks():
     assert lib.slapo_stack_fwd(C.byref(d), 2, tabs, 4096, None, 4096, None, 4096, 4096, None) == -1   # acts missing
     assert lib.slapo_stack_fwd(C.byref(d), 2, tabs, 4096, None, 4096, 4096, 4096, 4096, None) == -1   # NULL parameters
     assert lib.slapo_stack_bwd(C.byref(d), 0, tabs, 4096, None, 4096, 4096, 4096, 4096, tabs, 4096, None) == -2
+
+
+def test_llama_family_descriptor_and_pointer_checks():
+    base = dict(batch=2, seq=128, hidden=256, heads=4, ffn=1024, pre_ln=1, arch=B.LLAMA)
+    d = B.make_desc(**base)
+    saved, scratch = B.slapo_layer_workspace(d)
+    csaved, cscratch = B.slapo_layer_workspace(B.make_desc(**dict(base, arch=B.CLASSIC)))
+    T, F = 2 * 128, 1024
+    assert saved == csaved + T * F * 2                      # the factor pairs [T,2F] where the classic layer keeps act'(u) [T,F]
+    assert scratch >= cscratch + T * F * 2 + 128 * 32 * 8   # gradient pairs [T,2F] and the (cos, sin) table
+    for kw, code in [(dict(pre_ln=0), -3), (dict(rope_base=1.0), -2), (dict(rope_base=-5.0), -2), (dict(arch=2), -3)]:
+        with pytest.raises(B.SlapoError) as e:
+            B.slapo_layer_workspace(B.make_desc(**dict(base, **kw)))
+        assert e.value.status == code, (kw, e.value.status)
+    assert B.slapo_layer_saved_region(d, "dgate")[1] == 2 * T * F * 2
+    with pytest.raises(B.SlapoError):
+        B.slapo_layer_saved_region(d, "dact")
+    lib = B.lib()
+    # only the six weights and gains are required ...
+    params = B._Ptrs(**{n: (4096 if n in ("wqkv", "wo", "ln1_g", "w1", "w2", "ln2_g") else None) for n in B.PARAM_NAMES})
+    assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), 4096 + 4, None, 4096, 4096, 4096, None) == -4   # got past the NULL checks
+    params.w2 = None
+    assert lib.slapo_layer_fwd(C.byref(d), C.byref(params), 4096, None, 4096, 4096, 4096, None) == -1
+    # ... and the classic layer still wants all twelve
+    params.w2 = 4096
+    assert lib.slapo_layer_fwd(C.byref(B.make_desc(**dict(base, arch=B.CLASSIC))), C.byref(params), 4096, None, 4096, 4096, 4096, None) == -1
+    # gated epilogues: the pair layout needs N % 16 == 0 and its auxiliary buffer; rotary needs a LLaMA descriptor
+    assert lib.slapo_gemm(0, 0, 5, 0, 128, 136, 64, 4096, 4096, 4096, None, None, 4096, None) == -4
+    assert lib.slapo_gemm(0, 0, 5, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -1
+    assert lib.slapo_gemm(0, 1, 6, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -1
+    assert lib.slapo_gemm(0, 0, 7, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -3
+    assert lib.slapo_rope(C.byref(B.make_desc(**dict(base, arch=B.CLASSIC))), 4096, 4096, 0, None) == -3
+    assert lib.slapo_rope(C.byref(d), 4096, None, 0, None) == -1
