@@ -218,6 +218,115 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
   }
 }
 
+// The same backward for wide rows (H > 1024). The kernel above keeps a whole row and three column accumulators
+// per lane, which stops fitting the register file from H = 2048 on (it spills, and runs at a tenth of the
+// memory rate at H = 4096). Here the wavefronts of a block split the COLUMNS instead (thread c owns the 8
+// columns of chunk c, for every row the block visits) and walk the block's rows R at a time; the two per-row
+// sums cross the wavefronts through LDS, one barrier per R rows, added in wave order; the column sums never
+// leave their lane, so no reduction over wavefronts is needed at the end.
+template <typename T, bool LN, int R>
+__global__ __launch_bounds__(512) void bdrln_bwd_wide_kernel(
+    int64_t rows, int H, const T* __restrict__ dout, const T* __restrict__ z, const float* __restrict__ mu,
+    const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres_in,
+    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp) {
+  __shared__ float xs[2][R][8][2];   // [parity][row][wave][s1, s2]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int c = threadIdx.x;
+  const bool active = c < (H >> 3);
+  const float inv_h = 1.0f / (float)H;
+  float pg[8], pb[8], pd[8], g[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { pg[e] = pb[e] = pd[e] = 0.f; g[e] = 0.f; }
+  if (LN && active) load8(gamma + c * 8, g);
+  int par = 0;
+  for (int64_t row0 = (int64_t)blockIdx.x * R; row0 < rows; row0 += (int64_t)gridDim.x * R, par ^= 1) {
+    Raw8<T> rdy[R], rz[R], rres[R];
+    float m[R], rs[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {   // all loads of the R rows go out before anything waits
+      const int64_t row = row0 + j;
+      m[j] = 0.f; rs[j] = 0.f;
+      if (row < rows) {
+        if (active) {
+          rdy[j].load(dout + row * H + c * 8);
+          if (LN) rz[j].load(z + row * H + c * 8);
+          if (dres_in) rres[j].load(dres_in + row * H + c * 8);
+        }
+        if (LN) { m[j] = mu ? mu[row] : 0.f; rs[j] = rstd[row]; }   // no mu: RMSNorm
+      }
+    }
+    float dy[R][8], xh[R][8], s1[R], s2[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      s1[j] = 0.f; s2[j] = 0.f;
+      if (row0 + j < rows && active) {
+        rdy[j].get(dy[j]);
+        if (LN) {
+          float zz[8];
+          rz[j].get(zz);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            xh[j][e] = (zz[e] - m[j]) * rs[j];
+            pg[e] += dy[j][e] * xh[j][e];
+            pb[e] += dy[j][e];
+            dy[j][e] *= g[e];   // from here on dy holds dout * gamma
+            s1[j] += dy[j][e];
+            s2[j] += dy[j][e] * xh[j][e];
+          }
+        }
+      }
+    }
+    if (LN) {
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        const float a = wave_sum(s1[j]), b = wave_sum(s2[j]);
+        if (lane == 0) { xs[par][j][wave][0] = a; xs[par][j][wave][1] = b; }
+      }
+      __syncthreads();   // (the other parity is written next time round: no second barrier needed)
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        float a = 0.f, b = 0.f;
+        for (int w = 0; w < nw; ++w) { a += xs[par][j][w][0]; b += xs[par][j][w][1]; }
+        s1[j] = mu ? a * inv_h : 0.f;
+        s2[j] = b * inv_h;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      const int64_t row = row0 + j;
+      if (row < rows && active) {
+        const int64_t base = row * H;
+        float dz[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dz[e] = LN ? rs[j] * (dy[j][e] - s1[j] - xh[j][e] * s2[j]) : dy[j][e];
+        if (dres_in) {
+          float res[8];
+          rres[j].get(res);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dz[e] += res[e];
+        }
+        if (dz_out) store8(dz_out + base + c * 8, dz);
+        if (dr_out) {
+          const uint32_t keep = dropout_keep8(dp, (uint64_t)(base >> 3) + (uint64_t)c);
+          float dr[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            dr[e] = ((keep >> e) & 1u) ? dz[e] * dp.scale : 0.f;
+            pd[e] += dr[e];
+          }
+          store8(dr_out + base + c * 8, dr);
+        }
+      }
+    }
+  }
+  if (active) {
+    float* prow = partials + (size_t)blockIdx.x * 3 * H;
+    store8(prow + c * 8, pg);
+    store8(prow + H + c * 8, pb);
+    store8(prow + 2 * H + c * 8, pd);
+  }
+}
+
 // stage 1 of a column sum: block (bx, by) sums rows of slab by for the 32 chunks of column group bx
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partials_kernel(int64_t rows, int64_t N, const T* __restrict__ a,
@@ -343,6 +452,12 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
                        const void* gamma, const void* dres_in, void* dz_out, void* dr_out, float* partials,
                        const DropoutParams& dp, hipStream_t st) {
   const int blocks = bdrln_bwd_blocks(rows);
+  if (H / 8 > 128) {   // wide rows: columns split over the wavefronts of a block (H <= 4096: at most 8 of them)
+    const int waves = (H / 8 + 63) / 64;
+    hipLaunchKernelGGL((bdrln_bwd_wide_kernel<T, LN, 4>), dim3(blocks), dim3(waves * 64), 0, st, rows, H, (const T*)dout,
+                       (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp);
+    return;
+  }
 #define SLAPO_BWD(N, W)                                                                                      \
   do {                                                                                                       \
     auto kern = bdrln_bwd_kernel<T, N, LN, W>;                                                               \
@@ -353,10 +468,7 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
   } while (0)
   switch (nch_for(H)) {
     case 1: SLAPO_BWD(1, 8); break;
-    case 2: SLAPO_BWD(2, 8); break;
-    case 4: SLAPO_BWD(4, 8); break;
-    case 5: SLAPO_BWD(5, 4); break;
-    default: SLAPO_BWD(8, 4); break;
+    default: SLAPO_BWD(2, 8); break;
   }
 #undef SLAPO_BWD
 }

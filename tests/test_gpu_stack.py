@@ -11,6 +11,7 @@ import torch
 
 import workloads as W
 from oracle import layer as L
+from oracle import llama_layer as LL
 from paper_2302_08005_amd import binding as B
 from gpu_util import DEV, TOL, err
 
@@ -24,18 +25,21 @@ STACKS = [
                   pre_ln=1, config_id=22),
     W.LayerConfig("stack-postln-fp32", 1, 96, 128, 2, 512, causal=0, dropout_p=0.2, dtype=W.FP32, act=W.GELU,
                   config_id=23),
+    W.LayerConfig("stack-llama-bf16", 2, 128, 256, 2, 688, causal=1, dropout_p=0.1, dtype=W.BF16, pre_ln=1, ln_eps=1e-6,
+                  arch=W.LLAMA, config_id=24),
 ]
 
 
 def oracle_chain(cfg, params, x, sl, dy):
+    O = LL if cfg.arch == W.LLAMA else L
     caches, h = [], x.astype(np.float64)
     for l in range(N_LAYERS):
-        c = L.layer_forward(cfg.replace(layer_id=l), params[l], h, sl)
+        c = O.layer_forward(cfg.replace(layer_id=l), params[l], h, sl)
         caches.append(c)
         h = c["y"]
     grads, g = [None] * N_LAYERS, dy.astype(np.float64)
     for l in reversed(range(N_LAYERS)):
-        grads[l] = L.layer_backward(cfg.replace(layer_id=l), params[l], caches[l], g)
+        grads[l] = O.layer_backward(cfg.replace(layer_id=l), params[l], caches[l], g)
         g = grads[l]["dx"]
     return h, g, grads
 
@@ -55,7 +59,7 @@ def test_stack_matches_oracle_chain_and_single_layer_calls(cfg):
     tol = TOL[cfg.dtype]
     errs = {"y": err(y, y_ref), "dx": err(dx, dx_ref)}
     for l in range(N_LAYERS):
-        for k in W.PARAM_NAMES:
+        for k in W.param_names(cfg):
             errs[f"L{l}.d{k}"] = err(st.grads[l][k], g_ref[l][k])
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, (bad, errs)
@@ -69,7 +73,7 @@ def test_stack_matches_oracle_chain_and_single_layer_calls(cfg):
     g = dyd
     for l in reversed(range(N_LAYERS)):
         g = layers[l].backward(hs[l], sld, g)
-        for k in W.PARAM_NAMES:
+        for k in W.param_names(cfg):
             assert torch.equal(layers[l].grads[k], st.grads[l][k]), (l, k)
     assert torch.equal(g, dx)
 
@@ -88,7 +92,7 @@ def test_stack_matches_oracle_chain_and_single_layer_calls(cfg):
     torch.cuda.synchronize()
     assert torch.equal(y, y2) and torch.equal(dx, dx2)
     for l in range(N_LAYERS):
-        for k in W.PARAM_NAMES:
+        for k in W.param_names(cfg):
             assert torch.equal(ck.grads[l][k], st.grads[l][k]), (l, k)
 
 
