@@ -87,15 +87,17 @@ __device__ __forceinline__ GateTerms gate_terms(float u, float w) {
 // 16 t of the stage, so that a slab can be brought in either through registers or by the direct
 // global -> LDS loads of gfx950 (one wave-level load fills 1 KB of consecutive LDS, lane l at byte 16 l).
 // Bank conflicts are avoided by permuting, inside each tile row, which 16-byte chunk of global memory a
-// thread fetches. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte access, and 16
+// thread fetches. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte access, and 32
 // lanes of a transposing 8-byte read, are served together.
 //  - K-contiguous tile [rows][BK]: position p of row r holds chunk p ^ swzK(r), swzK(r) = (r / RP) % (BK/8),
 //    RP = rows per 256 B. A fragment read (one chunk of 16 consecutive rows) then lands in 16 different
 //    16-byte bank groups. swzK depends on the lane only (wave tiles start at multiples of 32 rows), so a
 //    fragment address is a per-lane base plus (2*ks ^ per-lane constant).
 //  - M-contiguous tile [BK][W]: position p of k-row r holds chunk p ^ (swzM(r) << 1), i.e. 32-byte granules
-//    are permuted by swzM(r) = (r / RPM) % min(W/16, 8), RPM = k-rows per 256 B. A transposing read (16
-//    lanes: 4 consecutive k-rows x 32 B) then finds its four rows in different bank groups.
+//    are permuted by swzM(r) (defined in the kernel). A transposing 8-byte read is served 32 lanes at a time:
+//    4 consecutive k-rows x 2 adjacent granules, whose 8 pieces the permutation spreads over the 8 bank
+//    groups (the conflict counter read 49 % of the LDS cycles with a permutation that only separated the
+//    four rows, 1 % of the K-contiguous level with this one).
 //
 // Why direct loads: a ds_write moves 64 B per clock and keeps the LDS busy meanwhile, so writing a slab
 // costs as much LDS time as reading it three times; measured on the chip, fragment reads running beside
@@ -137,6 +139,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
                                                                   const bf16_t* aux_in,
                                                                   bf16_t* __restrict__ aux_out, int act) {
   constexpr bool A_KC = (LAYOUT != GEMM_TN);  // A operand contiguous along K
+  constexpr bool DBUF = (LAYOUT == GEMM_TN);  // second fragment register set (measured: +7 % for TN, -4 % NN, -1 % NT)
   constexpr bool B_KC = (LAYOUT == GEMM_NT);
   // KS == 2: two sets of WGM x WGN wavefronts share the output tile; set g multiplies the g-th half of
   // every K slab and the two accumulator sets are added through LDS before the epilogue. This doubles the
@@ -158,8 +161,15 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   auto swzK = [](int row) { constexpr int RP = BK >= 128 ? 1 : 128 / BK; return (row / RP) % (BK / 8); };
   auto swzM = [](int krow, auto width) {
     constexpr int W = decltype(width)::value;
-    constexpr int RPM = W >= 128 ? 1 : 128 / W, MOD = W / 16 < 8 ? W / 16 : 8;
-    return (krow / RPM) % MOD;
+    static_assert(W >= 64, "at least four 32-byte granules per tile row");
+    constexpr int RPM = W >= 128 ? 1 : 128 / W;   // k-rows per 256 bytes of LDS
+    const int q = krow / RPM;
+    // One transposing read covers, per group of 32 lanes, four consecutive k-rows x two adjacent granules
+    // (an even one and its successor): eight 32-byte pieces that must land in eight different bank groups.
+    // The k-row picks bits 1-2 of the granule position (bit 1 only for 64-wide tiles, whose rows alternate
+    // between the two halves of the 256 bytes by themselves), so the granule's own low bit still tells
+    // the two halves apart; rows 8 apart (the other 32 lanes) differ in bit 0.
+    return W >= 128 ? (((q & 3) << 1) ^ ((q >> 3) & 1)) : (((q & 1) << 1) ^ ((q >> 2) & 1));
   };
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   bf16_t* sA = smem;               // [NSTG][SA]
@@ -335,6 +345,44 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   auto compute = [&](int stage) {
     const bf16_t* a = sA + stage * SA;
     const bf16_t* b = sB + stage * SB;
+    constexpr int KQ = BK / 16 / KS;
+    if constexpr (DBUF && TM * TN >= TM + TN && KQ >= 2) {
+      // Large wave tiles with both operands strided: one fragment of the NEXT k-step is requested in front of each
+      // of the first TM + TN MFMAs of the current one, into a second register set, in the order the next
+      // k-step uses them (A0, B0.., A1..). Every fragment then has at least six MFMAs of time, where the
+      // single-set schedule the compiler produces waits for its last B fragment two MFMAs after asking for it.
+      bf16x8_t fa[2][TM], fb[2][TN];
+      auto read_a = [&](int kq, int i) {
+        const int ks = kq + kgroup * KQ;
+        return A_KC ? frag_kc(a, fa_base, PA, i, ks) : frag_mc(a, ma_lo, ma_sw, PA, (wm0 >> 4) + 2 * i, ks);
+      };
+      auto read_b = [&](int kq, int j) {
+        const int ks = kq + kgroup * KQ;
+        return B_KC ? frag_kc(b, fb_base, PB, j, ks) : frag_mc(b, mb_lo, mb_sw, PB, (wn0 >> 4) + 2 * j, ks);
+      };
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[0][i] = read_a(0, i);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[0][j] = read_b(0, j);
+#pragma unroll
+      for (int kq = 0; kq < KQ; ++kq) {
+        const int cur = kq & 1, nxt = cur ^ 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int m = i * TN + j;   // MFMA index inside the k-step = slot of the next k-step to request
+            if (kq + 1 < KQ) {
+              if (m == 0) fa[nxt][0] = read_a(kq + 1, 0);
+              else if (m <= TN) fb[nxt][m - 1] = read_b(kq + 1, m - 1);
+              else if (m < TM + TN) fa[nxt][m - TN] = read_a(kq + 1, m - TN);
+            }
+            acc[i][j] = mfma16<F16>(fa[cur][i], fb[cur][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);   // keep this order (the scheduler would sink the requests)
+          }
+      }
+      return;
+    }
     // scheduling hint for the slab: interleave the LDS reads with the MFMAs (variant chosen by measurement)
     __builtin_amdgcn_iglp_opt(LAYOUT == GEMM_TN ? 1 : 0);
 #pragma unroll
