@@ -48,6 +48,71 @@ def event_time_ms(fn, iters, stream):
     return e0.elapsed_time(e1) / iters
 
 
+def torch_eager_step_ms(cfg, params, x, dy, seqlens, iters, stream):
+    """Context only: the same layer as an unfused chain of PyTorch library ops with autograd on the same GPU
+    (vendor GEMMs, the framework's attention, dropout, normalisation and activation kernels), the kind of
+    execution the paper's schedules start from. Returns milliseconds per forward+backward."""
+    import torch.nn.functional as F
+    dev = "cuda"
+    tdt = {W.FP32: torch.float32, W.FP16: torch.float16}.get(cfg.dtype, torch.bfloat16)
+    P = {k: torch.from_numpy(v).to(dev).to(tdt).requires_grad_(True) for k, v in params.items()}
+    xt = torch.from_numpy(x).to(dev).to(tdt).requires_grad_(True)
+    dyt = torch.from_numpy(dy).to(dev).to(tdt)
+    B_, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
+    d = H // h
+    mask = None
+    if seqlens is not None:
+        mask = (torch.arange(S, device=dev)[None, :] < torch.from_numpy(seqlens).to(dev)[:, None])[:, None, None, :]
+        if cfg.causal:
+            mask = mask & torch.tril(torch.ones(S, S, dtype=torch.bool, device=dev))[None, None]
+    llama = cfg.arch == W.LLAMA
+    if llama:
+        inv = 1.0 / (cfg.rope_base ** (torch.arange(0, d, 2, device=dev, dtype=torch.float32) / d))
+        ang = torch.outer(torch.arange(S, device=dev, dtype=torch.float32), inv)
+        cos, sin = ang.cos().to(tdt)[None, :, None, :], ang.sin().to(tdt)[None, :, None, :]
+
+        def rot(t):   # [B,S,h,d], adjacent pairs
+            e, o = t[..., 0::2], t[..., 1::2]
+            return torch.stack((e * cos - o * sin, e * sin + o * cos), dim=-1).reshape(t.shape)
+
+    def norm(t, k):
+        if llama:
+            return F.rms_norm(t, (H,), P[k + "_g"], cfg.ln_eps)
+        return F.layer_norm(t, (H,), P[k + "_g"], P[k + "_b"], cfg.ln_eps)
+
+    def layer(t):
+        a_in = norm(t, "ln1") if cfg.pre_ln else t
+        q, k, v = F.linear(a_in, P["wqkv"], P.get("bqkv")).split(H, dim=-1)
+        q, k, v = (u.reshape(B_, S, h, d) for u in (q, k, v))
+        if llama:
+            q, k = rot(q), rot(k)
+        q, k, v = (u.transpose(1, 2) for u in (q, k, v))
+        a = F.scaled_dot_product_attention(q, k, v, attn_mask=mask, dropout_p=cfg.attn_dropout_p,
+                                           is_causal=bool(cfg.causal) and mask is None)
+        a = a.transpose(1, 2).reshape(B_, S, H)
+        z1 = t + F.dropout(F.linear(a, P["wo"], P.get("bo")), cfg.dropout_p)
+        f_in = norm(z1, "ln2") if cfg.pre_ln else norm(z1, "ln1")
+        if llama:
+            uv = F.linear(f_in, P["w1"])
+            g = F.silu(uv[..., 0::2]) * uv[..., 1::2]
+        else:
+            u = F.linear(f_in, P["w1"], P["b1"])
+            g = F.gelu(u) if cfg.act == W.GELU else F.relu(u)
+        r2 = F.dropout(F.linear(g, P["w2"], P.get("b2")), cfg.dropout_p)
+        return z1 + r2 if cfg.pre_ln else norm(f_in + r2, "ln2")
+
+    def step():
+        for t in P.values():
+            t.grad = None
+        xt.grad = None
+        layer(xt).backward(dyt)
+
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    return event_time_ms(step, iters, stream)
+
+
 def cpu_baseline(cfg, params, x, dy, seqlens):
     """The fp64 oracle, as it stands, on the host cores: one full layer forward+backward."""
     if cfg.arch == W.LLAMA:
@@ -86,6 +151,8 @@ def main():
     ap.add_argument("--attn-dropout", type=float, default=0.0,
                     help="also drop attention probabilities with this probability (0 = the benchmark configuration)")
     ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
+    ap.add_argument("--eager-baseline", action="store_true",
+                    help="also time the same layer as unfused PyTorch library ops with autograd (context, in `extra`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -225,6 +292,9 @@ def main():
 
     if args.breakdown:
         breakdown(cfg, layer, xd, dyd, sld, stream)
+    if args.eager_baseline and cfg.n_layers == 1:
+        eager_ms = torch_eager_step_ms(cfg, params, x, dy, seqlens, max(10, args.steps // 2), stream)
+        extra["torch_eager_unfused"] = {"ms_per_step": eager_ms, "speedup_of_this_library": eager_ms / ms}
 
     out = {"metric": "layer fwd+bwd samples/s", "value": cfg.batch / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
