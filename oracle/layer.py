@@ -13,7 +13,9 @@ the listing in section 2.2 step 2) only when cfg.attn_dropout_p > 0, with its ow
 index ((b*heads + a)*S + i)*S + j); exact erf GeLU; biased
 variance and eps inside the square root for LayerNorm; key-padding mask hides keys j >= len_b from
 every query row; [Wq; Wk; Wv] stacked on the output dimension; pre-LN layers normalise the block
-inputs and have no LayerNorm after the second residual.
+inputs and have no LayerNorm after the second residual. The attention width heads * d may differ from the
+hidden size (cfg.attn_width): that is what one rank holds when the query/key/value and output projections are
+sharded along the heads (section 2.2 step 3); the packed projection is then [T, 3*width] and wo is [H, width].
 
 Tensors: x [B,S,H]; weights in [out, in] layout (Fig. 3 caption). Backward is derived by hand from
 these definitions and pinned by finite differences in the tests.
@@ -77,7 +79,7 @@ def attention_keep(cfg):
 
 def attention_fwd(cfg, qkv, seqlens):
     """qkv [T,3H] -> (A [T,H], P [B,h,S,S], LSE [B,h,S]). P is the softmax before dropout; A uses the dropped P."""
-    B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
+    B, S, H, h = cfg.batch, cfg.seq, cfg.attn_width, cfg.heads   # H: width of each of Q, K, V
     d = H // h
     keep = attention_keep(cfg)
     A = np.zeros((B * S, H))
@@ -106,7 +108,7 @@ def attention_fwd(cfg, qkv, seqlens):
 
 def attention_bwd(cfg, qkv, P, dA):
     """Gradient of attention_fwd's A w.r.t. the packed qkv."""
-    B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
+    B, S, H, h = cfg.batch, cfg.seq, cfg.attn_width, cfg.heads   # H: width of each of Q, K, V
     d = H // h
     dqkv = np.zeros_like(qkv)
     keep = attention_keep(cfg)

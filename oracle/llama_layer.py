@@ -20,7 +20,8 @@ from 0 inside each sequence; gate and up projections are stored as ONE matrix w1
 gate row c and row 2c+1 is up row c (so that one product yields both and a (gate, up) pair sits in adjacent
 columns); dropout (off in the LLaMA workload) keeps the classic layer's two sites and mask streams.
 
-Parameters: wqkv [3H,H], wo [H,H], ln1_g [H], w1 [2F,H], w2 [H,F], ln2_g [H].
+Parameters: wqkv [3W,H], wo [H,W], ln1_g [H], w1 [2F,H], w2 [H,F], ln2_g [H], with W = heads * d the attention
+width (= H unless the projections are sharded along the heads, cfg.attn_width).
 """
 import numpy as np
 
@@ -43,7 +44,7 @@ def rms_norm_bwd(dy, z, r, g):
 
 def rope_angles(cfg):
     """[S, d/2] rotation angles: position m, pair j -> m * base^(-2j/d)."""
-    d = cfg.hidden // cfg.heads
+    d = cfg.attn_width // cfg.heads
     theta = cfg.rope_base ** (-2.0 * np.arange(d // 2) / d)
     return np.arange(cfg.seq, dtype=np.float64)[:, None] * theta[None, :]
 
@@ -54,7 +55,7 @@ def rope_apply(cfg, qkv, inverse=False):
     ``inverse`` rotates by the negative angle: the transpose of the rotation, which is what carries a
     gradient w.r.t. the rotated vectors back to the unrotated ones.
     """
-    B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
+    B, S, H, h = cfg.batch, cfg.seq, cfg.attn_width, cfg.heads   # H: width of each of Q, K, V
     d = H // h
     ang = rope_angles(cfg)
     c, s = np.cos(ang), np.sin(ang)

@@ -16,6 +16,9 @@ VARIANTS = [dict(pre_ln=pl, act=act, causal=ca, len_hi=lh, len_lo=(2 if lh else 
 # with dropout on the attention probabilities (section 2.2 step 2 listing): padded encoder, causal pre-LN decoder
 VARIANTS += [dict(pre_ln=0, act=W.GELU, causal=0, len_hi=6, len_lo=3, attn_dropout_p=0.3, seq=8),
              dict(pre_ln=1, act=W.GELU, causal=1, len_hi=0, len_lo=0, attn_dropout_p=0.4, seq=8)]
+# attention width different from the hidden size (one rank's heads of a head-sharded layer; a wider inner width)
+VARIANTS += [dict(pre_ln=0, act=W.GELU, causal=0, len_hi=6, len_lo=2, heads=1, attn_dim=4),
+             dict(pre_ln=1, act=W.RELU, causal=1, len_hi=0, len_lo=0, heads=3, attn_dim=12)]
 
 
 def _setup(**kw):
@@ -61,8 +64,8 @@ def test_backward_matches_central_finite_differences(variant):
 
 def _torch_layer(cfg, tp, x, sl, M1, M2, MA=None):
     """The same layer built only from torch CPU fp64 library ops, the dropout masks entering as constants."""
-    B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
-    d = H // h
+    B, S, H, h, AW = cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.attn_width
+    d = AW // h
     scale = 1.0 / (1.0 - cfg.dropout_p)
     ok = torch.ones(B, 1, S, S, dtype=torch.bool)
     if cfg.causal:
@@ -72,7 +75,7 @@ def _torch_layer(cfg, tp, x, sl, M1, M2, MA=None):
     ln = lambda z, k: F.layer_norm(z, (H,), tp[k + "_g"], tp[k + "_b"], cfg.ln_eps)
     act = F.gelu if cfg.act == W.GELU else F.relu
     a_in = ln(x, "ln1") if cfg.pre_ln else x
-    q, k, v = F.linear(a_in, tp["wqkv"], tp["bqkv"]).split(H, dim=-1)
+    q, k, v = F.linear(a_in, tp["wqkv"], tp["bqkv"]).split(AW, dim=-1)
     heads = lambda t: t.reshape(B, S, h, d).transpose(1, 2)
     if MA is None:
         A = F.scaled_dot_product_attention(heads(q), heads(k), heads(v), attn_mask=ok)
@@ -80,7 +83,7 @@ def _torch_layer(cfg, tp, x, sl, M1, M2, MA=None):
         sc = (heads(q) @ heads(k).transpose(-1, -2)) / d ** 0.5
         pr = torch.softmax(sc.masked_fill(~ok, float("-inf")), dim=-1)
         A = (pr * MA / (1.0 - cfg.attn_dropout_p)) @ heads(v)
-    A = A.transpose(1, 2).reshape(B, S, H)
+    A = A.transpose(1, 2).reshape(B, S, AW)
     z1 = x + M1 * (F.linear(A, tp["wo"]) + tp["bo"]) * scale
     f_in = ln(z1, "ln2") if cfg.pre_ln else ln(z1, "ln1")
     r2 = F.linear(act(F.linear(f_in, tp["w1"], tp["b1"])), tp["w2"])
@@ -233,3 +236,23 @@ def test_attention_dropout_mask_stream_and_effect():
     assert np.allclose(P[b, a].sum(axis=-1), 1.0)          # P itself stays the undropped softmax
     A0, _, _ = L.attention_fwd(cfg.replace(attn_dropout_p=0.0), qkv, sl)
     assert np.array_equal(A0[b * S + i, a * d:(a + 1) * d], (P[b, a] @ v)[i])
+
+
+def test_head_sharded_attention_blocks_sum_to_the_full_block():
+    """Section 2.2 step 3: with the fused QKV and the output projection sharded along the heads, every rank runs
+    the attention block at width H/tp and the partial outputs add up to the unsharded block's."""
+    cfg, params, x, dy, sl = _setup(heads=4, hidden=8, causal=1, len_lo=3, len_hi=6)
+    full = L.layer_forward(cfg, params, x, sl)
+    H, h, d = cfg.hidden, cfg.heads, cfg.head_dim
+    for tp in (2, 4):
+        share = cfg.replace(heads=h // tp, attn_dim=H // tp)
+        assert share.head_dim == d and share.attn_width == H // tp
+        total = 0.0
+        for r in range(tp):
+            cols = np.arange(r * H // tp, (r + 1) * H // tp)                 # this rank's heads
+            rows = np.concatenate([cols, H + cols, 2 * H + cols])            # their Q, K and V rows of wqkv
+            qkv_r = full["X"] @ params["wqkv"][rows].T + params["bqkv"][rows]
+            a_r, _, lse_r = L.attention_fwd(share, qkv_r, sl)
+            assert np.array_equal(a_r, full["A"][:, cols]) and np.array_equal(lse_r, full["LSE"][:, r * h // tp:(r + 1) * h // tp])
+            total = total + a_r @ params["wo"][:, cols].T
+        assert np.abs(total - full["R1"]).max() < 1e-13

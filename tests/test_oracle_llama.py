@@ -11,7 +11,8 @@ from oracle import layer as L
 from oracle import llama_layer as LL
 
 VARIANTS = [dict(dropout_p=0.0), dict(dropout_p=0.25), dict(dropout_p=0.25, len_lo=2, len_hi=6),
-            dict(dropout_p=0.0, heads=1), dict(dropout_p=0.1, attn_dropout_p=0.3, seq=8)]
+            dict(dropout_p=0.0, heads=1), dict(dropout_p=0.1, attn_dropout_p=0.3, seq=8),
+            dict(dropout_p=0.0, heads=1, attn_dim=4), dict(dropout_p=0.25, heads=3, attn_dim=12)]   # attention width != hidden
 
 
 def _setup(**kw):
@@ -54,8 +55,8 @@ def test_backward_matches_central_finite_differences(variant):
 
 def _torch_layer(cfg, tp, x, sl, M1, M2, MA):
     """The same layer from torch CPU fp64 library ops; rotary embedding as a complex multiplication."""
-    B, S, H, h = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
-    d = H // h
+    B, S, H, h, AW = cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.attn_width
+    d = AW // h
     scale = 1.0 / (1.0 - cfg.dropout_p)
     inv_freq = 1.0 / (cfg.rope_base ** (torch.arange(0, d, 2, dtype=torch.float64) / d))
     phase = torch.polar(torch.ones(S, d // 2, dtype=torch.float64), torch.outer(torch.arange(S, dtype=torch.float64), inv_freq))
@@ -68,7 +69,7 @@ def _torch_layer(cfg, tp, x, sl, M1, M2, MA):
     if sl is not None:
         ok = ok & (torch.arange(S)[None, :] < torch.tensor(sl)[:, None])[:, None, None, :]
     n1 = F.rms_norm(x, (H,), tp["ln1_g"], cfg.ln_eps)
-    q, k, v = F.linear(n1, tp["wqkv"]).split(H, dim=-1)
+    q, k, v = F.linear(n1, tp["wqkv"]).split(AW, dim=-1)
     q = rotate(q.reshape(B, S, h, d)).transpose(1, 2)
     k = rotate(k.reshape(B, S, h, d)).transpose(1, 2)
     v = v.reshape(B, S, h, d).transpose(1, 2)
@@ -77,7 +78,7 @@ def _torch_layer(cfg, tp, x, sl, M1, M2, MA):
     else:
         pr = torch.softmax(((q @ k.transpose(-1, -2)) / d ** 0.5).masked_fill(~ok, float("-inf")), dim=-1)
         A = (pr * MA / (1.0 - cfg.attn_dropout_p)) @ v
-    A = A.transpose(1, 2).reshape(B, S, H)
+    A = A.transpose(1, 2).reshape(B, S, AW)
     z1 = x + M1 * F.linear(A, tp["wo"]) * scale
     n2 = F.rms_norm(z1, (H,), tp["ln2_g"], cfg.ln_eps)
     gate, up = F.linear(n2, tp["w1"][0::2]), F.linear(n2, tp["w1"][1::2])

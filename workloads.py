@@ -40,6 +40,7 @@ class LayerConfig:
     config_id: int = 0
     n_layers: int = 1
     arch: int = CLASSIC
+    attn_dim: int = 0             # heads * head_dim when it differs from hidden (one tensor-parallel rank's heads); 0 = hidden
     rope_base: float = 10000.0    # rotary base (LLAMA layers only)
 
     @property
@@ -47,8 +48,12 @@ class LayerConfig:
         return self.batch * self.seq
 
     @property
+    def attn_width(self) -> int:
+        return self.attn_dim or self.hidden
+
+    @property
     def head_dim(self) -> int:
-        return self.hidden // self.heads
+        return self.attn_width // self.heads
 
     def replace(self, **kw) -> "LayerConfig":
         return dataclasses.replace(self, **kw)
@@ -87,10 +92,10 @@ def param_names(cfg: LayerConfig) -> tuple:
 
 
 def param_shapes(cfg: LayerConfig) -> dict:
-    H, F = cfg.hidden, cfg.ffn
+    H, F, A = cfg.hidden, cfg.ffn, cfg.attn_width
     if cfg.arch == LLAMA:   # w1 holds gate (even rows) and up (odd rows) projections
-        return {"wqkv": (3 * H, H), "wo": (H, H), "ln1_g": (H,), "w1": (2 * F, H), "w2": (H, F), "ln2_g": (H,)}
-    return {"wqkv": (3 * H, H), "bqkv": (3 * H,), "wo": (H, H), "bo": (H,), "ln1_g": (H,), "ln1_b": (H,),
+        return {"wqkv": (3 * A, H), "wo": (H, A), "ln1_g": (H,), "w1": (2 * F, H), "w2": (H, F), "ln2_g": (H,)}
+    return {"wqkv": (3 * A, H), "bqkv": (3 * A,), "wo": (H, A), "bo": (H,), "ln1_g": (H,), "ln1_b": (H,),
             "w1": (F, H), "b1": (F,), "w2": (H, F), "b2": (H,), "ln2_g": (H,), "ln2_b": (H,)}
 
 
