@@ -29,10 +29,10 @@ TRAFFIC_BYTES_PER_LAUNCH = {"C2-bert-large-layer-bf16": 108.45e6}   # 100.76 MB 
 def layer_flops(cfg, seqlens):
     """Algorithmic FLOPs of one layer forward+backward: 3 x GEMM + 3.5 x visible attention."""
     T, H, F, S = cfg.tokens, cfg.hidden, cfg.ffn, cfg.seq
-    gemm_fwd = 2.0 * T * (4.0 * H * H + (3.0 if cfg.arch == W.LLAMA else 2.0) * H * F)   # gated FFN: three F x H products
+    gemm_fwd = 2.0 * T * (4.0 * H * cfg.attn_width + (3.0 if cfg.arch == W.LLAMA else 2.0) * H * F)   # gated FFN: three F x H products
     lens = [S] * cfg.batch if seqlens is None else [int(v) for v in seqlens]
     phi = 0.5 * (1.0 + 1.0 / S) if cfg.causal else 1.0
-    att_fwd = sum(4.0 * H * S * l * phi for l in lens)
+    att_fwd = sum(4.0 * cfg.attn_width * S * l * phi for l in lens)
     return 3.0 * gemm_fwd + 3.5 * att_fwd, gemm_fwd, att_fwd
 
 
@@ -151,6 +151,9 @@ def main():
     ap.add_argument("--attn-dropout", type=float, default=0.0,
                     help="also drop attention probabilities with this probability (0 = the benchmark configuration)")
     ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
+    ap.add_argument("--tp", type=int, default=1,
+                    help="time ONE rank's share of the layer sharded N ways along heads and FFN columns "
+                         "(heads/N, attention width hidden/N, ffn/N; no collectives are run)")
     ap.add_argument("--eager-baseline", action="store_true",
                     help="also time the same layer as unfused PyTorch library ops with autograd (context, in `extra`)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -170,6 +173,11 @@ def main():
         cfg = cfg.replace(attn_dropout_p=args.attn_dropout)
     if args.fp16:
         cfg = cfg.replace(dtype=W.FP16)
+    if args.tp > 1:
+        if cfg.heads % args.tp or cfg.ffn % (8 * args.tp):
+            sys.exit(f"bench.py: --tp {args.tp} does not divide {cfg.heads} heads / ffn {cfg.ffn}")
+        cfg = cfg.replace(name=f"{cfg.name}-tp{args.tp}-share", heads=cfg.heads // args.tp, attn_dim=cfg.hidden // args.tp,
+                          ffn=cfg.ffn // args.tp)
     params = W.make_params(cfg)
     x, dy, seqlens = W.make_inputs(cfg)
     layer = B.Layer(cfg, params, checkpoint=1 if args.checkpoint else 0)
@@ -224,7 +232,7 @@ def main():
     mk = lambda *shape: torch.randn(*shape, device="cuda", dtype=torch.float32).to(tdt)
     llama = cfg.arch == W.LLAMA
     F1 = 2 * F if llama else F                                  # rows of w1 (gate and up rows interleaved)
-    tn_shapes = [(H, F, T), (F1, H, T), (3 * H, H, T)]         # (M, N, K): C[M,N] = A[K,M]^T B[K,N]
+    tn_shapes = [(H, F, T), (F1, H, T), (3 * cfg.attn_width, H, T)]   # (M, N, K): C[M,N] = A[K,M]^T B[K,N]
     tn_bufs = [(mk(K, M), mk(K, N), torch.empty(M, N, device="cuda", dtype=tdt)) for (M, N, K) in tn_shapes]
 
     def dominant():
@@ -303,7 +311,7 @@ def main():
            "config": {"workload": cfg.name, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                       "heads": cfg.heads, "ffn": cfg.ffn, "causal": cfg.causal, "dropout_p": cfg.dropout_p,
                       "attn_dropout_p": cfg.attn_dropout_p, "pre_ln": cfg.pre_ln, "layers": cfg.n_layers, "checkpoint": int(args.checkpoint),
-                      "family": "llama" if llama else "classic",
+                      "family": "llama" if llama else "classic", "tp_share": args.tp,
                       "parallelism": "single-gpu"},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:

@@ -58,8 +58,8 @@ enum { SLAPO_GELU_ERF = 0, SLAPO_RELU = 1 };
  * and no bias anywhere. */
 enum { SLAPO_ARCH_CLASSIC = 0, SLAPO_ARCH_LLAMA = 1 };
 
-/* Layer description (host struct). hidden/heads must be 64 or 128; hidden, ffn multiples of 8;
- * hidden <= 4096. */
+/* Layer description (host struct). The head dim (hidden/heads, or attn_dim/heads) must be 64 or 128; hidden,
+ * ffn multiples of 8; hidden <= 4096. */
 typedef struct {
   int32_t batch, seq, hidden, heads, ffn;
   int32_t causal;           /* 1: query i sees keys j <= i                                     */
@@ -84,6 +84,13 @@ typedef struct {
                                ((b*heads + a)*seq + i)*seq + j; needs seq % 8 == 0). 0 = none.     */
   int32_t arch;             /* SLAPO_ARCH_CLASSIC | SLAPO_ARCH_LLAMA (needs pre_ln = 1; act is ignored) */
   float rope_base;          /* LLAMA: base of the rotary frequencies (10000 in the published models), > 1 */
+  int32_t attn_dim;         /* width W = heads * head dim of each of Q, K, V when it differs from hidden; 0 = hidden.
+                               W/heads must be 64 or 128. With W != hidden, wqkv is [3W,hidden], bqkv [3W], wo
+                               [hidden,W], and every "[.., 3H]" / attention "[.., H]" shape below reads 3W / W.
+                               This is one rank's share of a layer whose fused QKV and output projections are
+                               sharded along the heads (section 2.2 step 3): heads/tp heads, W = hidden/tp, and
+                               ffn = F/tp for the feed-forward shards; the all-reduces between the shares are the
+                               caller's (the output is then this rank's partial layer, biases included).      */
 } slapo_layer_desc;
 
 /* Parameters: wqkv [3H,H] = [Wq;Wk;Wv] stacked on the output dim, bqkv [3H], wo [H,H], bo [H],

@@ -23,7 +23,7 @@ class LayerDesc(C.Structure):
                 ("ffn", C.c_int32), ("causal", C.c_int32), ("dropout_p", C.c_float), ("seed", C.c_uint64),
                 ("dtype", C.c_int32), ("act", C.c_int32), ("pre_ln", C.c_int32), ("layer_id", C.c_int32),
                 ("ln_eps", C.c_float), ("accumulate_grads", C.c_int32), ("checkpoint", C.c_int32), ("attn_dropout_p", C.c_float),
-                ("arch", C.c_int32), ("rope_base", C.c_float)]
+                ("arch", C.c_int32), ("rope_base", C.c_float), ("attn_dim", C.c_int32)]
 
 
 class _Ptrs(C.Structure):
@@ -105,7 +105,7 @@ def make_desc(cfg=None, **kw) -> LayerDesc:
     """Builds a descriptor from a workloads.LayerConfig-like object and/or keyword overrides."""
     vals = dict(batch=1, seq=1, hidden=64, heads=1, ffn=64, causal=0, dropout_p=0.0, seed=0, dtype=BF16, act=GELU,
                 pre_ln=0, layer_id=0, ln_eps=1e-5, accumulate_grads=0, checkpoint=0, attn_dropout_p=0.0,
-                arch=CLASSIC, rope_base=10000.0)
+                arch=CLASSIC, rope_base=10000.0, attn_dim=0)
     if cfg is not None:
         for k in vals:
             if hasattr(cfg, k):

@@ -15,14 +15,17 @@ namespace {
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// width of each of Q, K, V (heads * head dim): the hidden size unless the descriptor says otherwise
+inline int attn_width(const slapo_layer_desc* d) { return d->attn_dim > 0 ? d->attn_dim : d->hidden; }
+
 int check_desc(const slapo_layer_desc* d) {
   if (!d) return SLAPO_ERR_NULL;
-  if (d->batch <= 0 || d->seq <= 0 || d->hidden <= 0 || d->heads <= 0 || d->ffn <= 0) return SLAPO_ERR_SHAPE;
-  if (d->hidden % d->heads != 0) return SLAPO_ERR_SHAPE;
+  if (d->batch <= 0 || d->seq <= 0 || d->hidden <= 0 || d->heads <= 0 || d->ffn <= 0 || d->attn_dim < 0) return SLAPO_ERR_SHAPE;
+  if (attn_width(d) % d->heads != 0) return SLAPO_ERR_SHAPE;
   if (!(d->dropout_p >= 0.f && d->dropout_p < 1.f)) return SLAPO_ERR_SHAPE;
   if (!(d->ln_eps > 0.f)) return SLAPO_ERR_SHAPE;
   if (d->hidden % 8 != 0 || d->ffn % 8 != 0) return SLAPO_ERR_ALIGN;
-  const int hd = d->hidden / d->heads;
+  const int hd = attn_width(d) / d->heads;
   if (hd != 64 && hd != 128) return SLAPO_ERR_UNSUPPORTED;
   if (d->hidden > 4096) return SLAPO_ERR_UNSUPPORTED;
   if (d->dtype != SLAPO_BF16 && d->dtype != SLAPO_FP32 && d->dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
@@ -32,6 +35,7 @@ int check_desc(const slapo_layer_desc* d) {
   if (!(d->attn_dropout_p >= 0.f && d->attn_dropout_p < 1.f)) return SLAPO_ERR_SHAPE;
   if (d->attn_dropout_p > 0.f && d->seq % 8 != 0) return SLAPO_ERR_ALIGN;   // a mask block of 8 keys stays inside one query row
   if ((int64_t)d->batch * d->seq * 3 * d->hidden >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  if ((int64_t)d->batch * d->seq * 3 * attn_width(d) >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->seq * d->ffn >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if (d->arch != SLAPO_ARCH_CLASSIC && d->arch != SLAPO_ARCH_LLAMA) return SLAPO_ERR_UNSUPPORTED;
   if (d->arch == SLAPO_ARCH_LLAMA) {
@@ -67,7 +71,7 @@ DropoutParams make_dropout(const slapo_layer_desc* d, int site) {
 }
 
 AttnShape make_attn_shape(const slapo_layer_desc* d) {
-  AttnShape as = {d->batch, d->seq, d->hidden, d->heads, d->causal};
+  AttnShape as = {d->batch, d->seq, attn_width(d), d->heads, d->causal};
   as.drop.key0 = (uint32_t)(d->seed & 0xffffffffu);
   as.drop.key1 = (uint32_t)(d->seed >> 32);
   as.drop.site = 2u;
@@ -116,12 +120,12 @@ struct SavedLayout {
 };
 SavedLayout saved_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
-  const size_t T = (size_t)d->batch * d->seq, H = d->hidden, F = d->ffn;
+  const size_t T = (size_t)d->batch * d->seq, H = d->hidden, F = d->ffn, A = attn_width(d);
   SavedLayout L;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };
-  L.qkv = take(T * 3 * H * eb);
-  L.attn = take(T * H * eb);
+  L.qkv = take(T * 3 * A * eb);
+  L.attn = take(T * A * eb);
   L.lse = take((size_t)d->batch * d->heads * d->seq * 4);
   L.z1 = take(T * H * eb);
   L.n1 = d->pre_ln ? take(T * H * eb) : (size_t)-1;
@@ -142,22 +146,22 @@ struct ScratchLayout {
 };
 ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
-  const size_t T = (size_t)d->batch * d->seq, H = d->hidden, F = d->ffn;
+  const size_t T = (size_t)d->batch * d->seq, H = d->hidden, F = d->ffn, A = attn_width(d);
   ScratchLayout L;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align256(o + bytes); return at; };
-  L.t0 = take(T * H * eb);
+  L.t0 = take(T * (H > A ? H : A) * eb);   // also holds the gradient of the attention output [T,A]
   L.t1 = take(T * H * eb);
   L.t2 = take(T * H * eb);
   L.t3 = take(T * H * eb);
   L.du = take(T * F * eb * (is_llama(d) ? 2 : 1));
-  L.dqkv = take(T * 3 * H * eb);
+  L.dqkv = take(T * 3 * A * eb);
   L.delta = take((size_t)d->batch * d->heads * d->seq * 4);
   L.part_row = take((size_t)bdrln_bwd_blocks((int64_t)T) * 3 * H * 4);
-  const size_t widest = F > 3 * H ? F : 3 * H;
+  const size_t widest = F > 3 * A ? F : 3 * A;
   L.part_col = take((size_t)colsum_blocks((int64_t)T) * widest * 4);
   L.part_col2 = take((size_t)colsum_blocks((int64_t)T) * widest * 4);   // the two streams of backward each own one
-  L.rope = is_llama(d) ? take((size_t)d->seq * (d->hidden / d->heads / 2) * 8) : 0;   // (cos, sin) table
+  L.rope = is_llama(d) ? take((size_t)d->seq * (A / d->heads / 2) * 8) : 0;   // (cos, sin) table
   // checkpoint mode: the activations that forward would hand to backward live here instead, for the
   // duration of one call only (backward recomputes them), so the caller keeps nothing per layer but x
   L.acts = d->checkpoint ? take(saved_layout(d).total) : 0;
@@ -197,10 +201,10 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
   if (rc) return rc;
   const SavedLayout L = saved_layout(desc);
   const size_t eb = desc->dtype == SLAPO_FP32 ? 4 : 2;
-  const size_t T = (size_t)desc->batch * desc->seq, H = desc->hidden, F = desc->ffn;
+  const size_t T = (size_t)desc->batch * desc->seq, H = desc->hidden, F = desc->ffn, A = attn_width(desc);
   size_t off = (size_t)-1, len = 0;
-  if (!strcmp(name, "qkv")) { off = L.qkv; len = T * 3 * H * eb; }
-  else if (!strcmp(name, "attn")) { off = L.attn; len = T * H * eb; }
+  if (!strcmp(name, "qkv")) { off = L.qkv; len = T * 3 * A * eb; }
+  else if (!strcmp(name, "attn")) { off = L.attn; len = T * A * eb; }
   else if (!strcmp(name, "lse")) { off = L.lse; len = (size_t)desc->batch * desc->heads * desc->seq * 4; }
   else if (!strcmp(name, "z1")) { off = L.z1; len = T * H * eb; }
   else if (!strcmp(name, "n1")) { off = L.n1; len = T * H * eb; }
@@ -225,7 +229,7 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
 static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
                         void* y, void* saved, void* scratch, hipStream_t st) {
   const int dt = d->dtype;   // SLAPO_* element types are the launch interface's DT_* values
-  const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
+  const int T = d->batch * d->seq, H = d->hidden, F = d->ffn, A = attn_width(d);
   const SavedLayout L = saved_layout(d);
   const ScratchLayout W = scratch_layout(d);
   char* sv = (char*)saved;
@@ -248,14 +252,14 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   if (llama) {
     // no biases; queries and keys are rotated in place by their position before the attention reads them
     float* table = (float*)(sc + W.rope);
-    launch_rope_table(d->seq, H / d->heads, d->rope_base, table, st);
-    launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, nullptr, nullptr, nullptr, st);
-    launch_rope(dt, T, d->seq, H, H / d->heads, table, qkv, 0, st);
+    launch_rope_table(d->seq, A / d->heads, d->rope_base, table, st);
+    launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, 3 * A, H, attn_in, p->wqkv, qkv, nullptr, nullptr, nullptr, st);
+    launch_rope(dt, T, d->seq, A, A / d->heads, table, qkv, 0, st);
   } else {
-    launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * H, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
+    launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * A, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
   }
   launch_attn_fwd(dt, as, qkv, seqlens, attn, lse, st);
-  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, H, attn, p->wo, r, nullptr, nullptr, nullptr, st);
+  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, A, attn, p->wo, r, nullptr, nullptr, nullptr, st);
   const void* bo = llama ? nullptr : p->bo;
   const void* b2 = llama ? nullptr : p->b2;
   if (d->pre_ln) launch_bdrln_fwd(dt, T, H, r, bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, rms, st);
@@ -299,7 +303,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
 
   hipStream_t st = (hipStream_t)stream;
   const int dt = d->dtype, acc = d->accumulate_grads ? 1 : 0;
-  const int T = d->batch * d->seq, H = d->hidden, F = d->ffn;
+  const int T = d->batch * d->seq, H = d->hidden, F = d->ffn, A = attn_width(d);
   const SavedLayout L = saved_layout(d);
   const ScratchLayout W = scratch_layout(d);
   if (d->checkpoint) {
@@ -380,28 +384,28 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     reduce_rows(gr->ln1_g, g_ln1_b, g_bo);
   }
   fork(2);
-  dweight(H, H, t3, attn, gr->wo);
-  launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
+  dweight(H, A, t3, attn, gr->wo);
+  launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, A, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
   launch_attn_bwd(dt, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
   if (llama) {
     // the attention gradients are w.r.t. the rotated queries and keys: turn them back (the rotation's transpose)
     float* table = (float*)(sc + W.rope);
-    if (!d->checkpoint) launch_rope_table(d->seq, H / d->heads, d->rope_base, table, st);   // else the recomputed forward just wrote it
-    launch_rope(dt, T, d->seq, H, H / d->heads, table, dqkv, 1, st);
+    if (!d->checkpoint) launch_rope_table(d->seq, A / d->heads, d->rope_base, table, st);   // else the recomputed forward just wrote it
+    launch_rope(dt, T, d->seq, A, A / d->heads, table, dqkv, 1, st);
   }
   fork(3);
   if (d->pre_ln) {
-    dweight(3 * H, H, dqkv, sv + L.n1, gr->wqkv);
-    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * H, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
+    dweight(3 * A, H, dqkv, sv + L.n1, gr->wqkv);
+    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * A, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
     launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, rms, st);
     reduce_rows(gr->ln1_g, g_ln1_b, nullptr);
   } else {
-    dweight(3 * H, H, dqkv, x, gr->wqkv);
-    launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * H, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
+    dweight(3 * A, H, dqkv, x, gr->wqkv);
+    launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * A, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
   }
   // the last bias gradient goes behind the data gradient on the caller's stream: the helper stream's last
   // product is the longer one, and this way the two streams end at about the same time
-  if (!llama) colsum(dqkv, 3 * H, gr->bqkv, st);
+  if (!llama) colsum(dqkv, 3 * A, gr->bqkv, st);
   if (side) {   // join: the caller's stream continues only after the weight gradients are complete
     (void)hipEventRecord(side->join, ws);
     (void)hipStreamWaitEvent(st, side->join, 0);
@@ -553,9 +557,9 @@ int slapo_rope(const slapo_layer_desc* d, void* qkv, float* table, int inverse, 
   if (!is_llama(d)) return SLAPO_ERR_UNSUPPORTED;
   if (!qkv || !table) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(table)) return SLAPO_ERR_ALIGN;
-  const int hd = d->hidden / d->heads;
+  const int hd = attn_width(d) / d->heads;
   launch_rope_table(d->seq, hd, d->rope_base, table, (hipStream_t)stream);
-  launch_rope(d->dtype, (int64_t)d->batch * d->seq, d->seq, d->hidden, hd, table, qkv, inverse ? 1 : 0, (hipStream_t)stream);
+  launch_rope(d->dtype, (int64_t)d->batch * d->seq, d->seq, attn_width(d), hd, table, qkv, inverse ? 1 : 0, (hipStream_t)stream);
   return finish();
 }
 

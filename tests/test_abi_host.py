@@ -124,3 +124,19 @@ def test_llama_family_descriptor_and_pointer_checks():
     assert lib.slapo_gemm(0, 0, 7, 0, 128, 128, 64, 4096, 4096, 4096, None, None, None, None) == -3
     assert lib.slapo_rope(C.byref(B.make_desc(**dict(base, arch=B.CLASSIC))), 4096, 4096, 0, None) == -3
     assert lib.slapo_rope(C.byref(d), 4096, None, 0, None) == -1
+
+
+def test_attention_width_other_than_hidden():
+    base = dict(batch=2, seq=128, hidden=512, heads=4, ffn=1024)
+    full = B.slapo_layer_workspace(B.make_desc(**base))
+    share = B.slapo_layer_workspace(B.make_desc(**dict(base, heads=2, attn_dim=256)))     # half the heads of width 128
+    T = 2 * 128
+    assert full[0] - share[0] == T * (3 + 1) * 256 * 2 + T * 2 * 4   # packed projection, attention output, and the lse of two heads
+    d = B.make_desc(**dict(base, heads=2, attn_dim=256))
+    assert B.slapo_layer_saved_region(d, "qkv")[1] == T * 3 * 256 * 2 and B.slapo_layer_saved_region(d, "attn")[1] == T * 256 * 2
+    wide = B.slapo_layer_workspace(B.make_desc(**dict(base, heads=6, attn_dim=768)))
+    assert wide[0] > full[0] and wide[1] > full[1]
+    for kw, code in [(dict(heads=3, attn_dim=256), -2), (dict(heads=2, attn_dim=64), -3), (dict(attn_dim=-8), -2)]:
+        with pytest.raises(B.SlapoError) as e:
+            B.slapo_layer_workspace(B.make_desc(**dict(base, **kw)))
+        assert e.value.status == code, (kw, e.value.status)

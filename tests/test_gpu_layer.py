@@ -28,6 +28,11 @@ SMALL = [
                   len_lo=50, len_hi=200, layer_id=2, config_id=14),
     W.LayerConfig("attn-dropout-bf16-preln-causal-d128", 2, 264, 512, 4, 1536, causal=1, dropout_p=0.1, attn_dropout_p=0.2,
                   dtype=W.BF16, pre_ln=1, config_id=15),
+    # attention width != hidden: one of two ranks of a head-sharded layer (2 of 4 heads of 128, half the FFN), and a wider one
+    W.LayerConfig("tp2-share-bf16", 2, 200, 512, 2, 1024, causal=0, dropout_p=0.1, dtype=W.BF16, attn_dim=256,
+                  len_lo=60, len_hi=200, config_id=17),
+    W.LayerConfig("wide-attention-fp32-preln-causal", 2, 96, 256, 6, 520, causal=1, dropout_p=0.1, dtype=W.FP32, pre_ln=1,
+                  attn_dim=384, config_id=18),
 ]
 
 
@@ -111,7 +116,7 @@ def test_zero_dropout_matches_layer_without_dropout_bitwise():
     assert torch.equal(y, y2)
 
 
-@pytest.mark.parametrize("idx", [0, 2, 4, 10])
+@pytest.mark.parametrize("idx", [0, 2, 4, 10, 13])
 def test_checkpoint_mode_recomputes_to_the_same_bits(idx):
     """Activation checkpointing: no saved buffer, backward recomputes the forward; everything bit-identical."""
     cfg = SMALL[idx]

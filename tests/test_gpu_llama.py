@@ -115,6 +115,9 @@ SMALL = [
                   arch=W.LLAMA, config_id=25),
     W.LayerConfig("llama-bf16-bidirectional-base500", 2, 128, 256, 4, 512, causal=0, dropout_p=0.0, dtype=W.BF16, pre_ln=1,
                   ln_eps=1e-5, arch=W.LLAMA, rope_base=500.0, config_id=26),
+    # one of four ranks of a head-sharded layer: 2 of 8 heads, a quarter of the FFN
+    W.LayerConfig("llama-bf16-tp4-share", 2, 128, 512, 2, 344, causal=1, dropout_p=0.0, dtype=W.BF16, pre_ln=1, ln_eps=1e-6,
+                  arch=W.LLAMA, attn_dim=128, config_id=27),
 ]
 SAVED = {"qkv": "QKV", "attn": "A", "z1": "Z1", "n1": "N1", "n2": "N2", "g": "G", "lse": "LSE", "rstd1": "r1", "rstd2": "r2"}
 
