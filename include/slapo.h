@@ -21,7 +21,7 @@
  *     slapo_layer_bwd issues its weight-gradient GEMMs on one internal helper stream per device, created
  *     on first use and kept for the life of the process, forked from and joined back into `stream` with
  *     events (capturable in a HIP graph like any fork/join); SLAPO_SINGLE_STREAM=1 in the environment
- *     keeps everything on `stream`. This helper stream is the only state the library holds.
+ *     keeps everything on `stream` (and SLAPO_NO_SPLITK=1 turns the K-range weight gradients off: A/B timing). This helper stream is the only state the library holds.
  *   - Return value: SLAPO_OK (0) or a negative slapo_status. Argument checks run before the first
  *     HIP call, so they behave the same on a host without a GPU. Nothing throws or aborts.
  *   - Same inputs and seed give bitwise identical outputs (no floating-point atomics anywhere).
@@ -181,6 +181,16 @@ const char *slapo_status_string(int status);
 int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K,
                const void *A, const void *B, void *C, const void *bias, const void *aux_in,
                void *aux_out, void *stream);
+
+/* Weight gradient C[M,N] (+)= A[K,M]^T B[K,N] (layout 2 with K = tokens; accumulate != 0 adds to C). When the
+ * output has too few 128x128 tiles to fill the chip and K is a long multiple of 256 (at least 6144), the product is
+ * computed in up to 8 K ranges at once, as fp32 partial tiles in `ws` that a second kernel adds in range order (bitwise
+ * reproducible). slapo_weight_grad_workspace writes the bytes of `ws` a shape wants (0: the plain GEMM is used
+ * and ws may be NULL; also for SLAPO_FP32). ws: device, 16-byte aligned, free again when the call's work is done.
+ * slapo_layer_bwd uses this path for its four weight gradients with a region of its scratch buffer. */
+int slapo_weight_grad_workspace(int dtype, int64_t M, int64_t N, int64_t K, size_t *ws_bytes);
+int slapo_weight_grad(int dtype, int accumulate, int64_t M, int64_t N, int64_t K, const void *A, const void *B,
+                      void *C, void *ws, void *stream);
 
 /* Fused softmax attention over the packed projection qkv [B,S,3H] (Q | K | V on the last axis,
  * head a owning columns a*d..a*d+d-1 of each): out [B,S,H], lse [B,heads,S] fp32 holding

@@ -69,6 +69,8 @@ def lib():
             "slapo_colreduce_partials": [i32, i64, i64, i64, vp, vp, i32, vp],
             "slapo_dropout_mask": [dp, i32, i64, vp, vp],
             "slapo_rope": [dp, vp, vp, i32, vp],
+            "slapo_weight_grad_workspace": [i32, i64, i64, i64, C.POINTER(C.c_size_t)],
+            "slapo_weight_grad": [i32, i32, i64, i64, i64, vp, vp, vp, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -150,6 +152,17 @@ def slapo_layer_bwd(desc, params: dict, x, seqlens, dy, saved, dx, grads: dict, 
 def slapo_gemm(dtype, layout, epilogue, act, M, N, K, A, B, Cout, bias=None, aux_in=None, aux_out=None, stream=None):
     _check(lib().slapo_gemm(dtype, layout, epilogue, act, M, N, K, _p(A), _p(B), _p(Cout), _p(bias), _p(aux_in),
                             _p(aux_out), _stream(stream)), "slapo_gemm")
+
+
+def slapo_weight_grad_workspace(dtype, M, N, K) -> int:
+    a = C.c_size_t(0)
+    _check(lib().slapo_weight_grad_workspace(dtype, M, N, K, C.byref(a)), "slapo_weight_grad_workspace")
+    return a.value
+
+
+def slapo_weight_grad(dtype, accumulate, M, N, K, A, B, Cout, ws=None, stream=None):
+    _check(lib().slapo_weight_grad(dtype, accumulate, M, N, K, _p(A), _p(B), _p(Cout), _p(ws), _stream(stream)),
+           "slapo_weight_grad")
 
 
 def slapo_attn_fwd(desc, qkv, seqlens, out, lse, stream=None):

@@ -142,7 +142,7 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
 }
 
 struct ScratchLayout {
-  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, rope, acts, total;
+  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, rope, splitk, acts, total;
 };
 ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
@@ -162,6 +162,16 @@ ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   L.part_col = take((size_t)colsum_blocks((int64_t)T) * widest * 4);
   L.part_col2 = take((size_t)colsum_blocks((int64_t)T) * widest * 4);   // the two streams of backward each own one
   L.rope = is_llama(d) ? take((size_t)d->seq * (A / d->heads / 2) * 8) : 0;   // (cos, sin) table
+  // fp32 partial tiles of the weight gradients that are computed in several K ranges (one at a time: all of them
+  // run on the helper stream); 0 for shapes that fill the chip with plain tiles
+  {
+    const int Ti = (int)T, Hi = (int)H, Fi = (int)F, Ai = (int)A, F1 = is_llama(d) ? 2 * Fi : Fi;
+    size_t w = weight_grad_ws_bytes(d->dtype, Hi, Fi, Ti);
+    const size_t w1 = weight_grad_ws_bytes(d->dtype, F1, Hi, Ti), wo = weight_grad_ws_bytes(d->dtype, Hi, Ai, Ti);
+    const size_t wq = weight_grad_ws_bytes(d->dtype, 3 * Ai, Hi, Ti);
+    w = w > w1 ? w : w1; w = w > wo ? w : wo; w = w > wq ? w : wq;
+    L.splitk = w ? take(w) : 0;
+  }
   // checkpoint mode: the activations that forward would hand to backward live here instead, for the
   // duration of one call only (backward recomputes them), so the caller keeps nothing per layer but x
   L.acts = d->checkpoint ? take(saved_layout(d).total) : 0;
@@ -332,8 +342,9 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     if (side) { (void)hipEventRecord(side->fork[i], st); (void)hipStreamWaitEvent(ws, side->fork[i], 0); }
   };
   // weight gradient: C (+)= A^T B
+  float* splitk_ws = W.splitk ? (float*)(sc + W.splitk) : nullptr;
   auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
-    launch_gemm(dt, GEMM_TN, acc ? EPI_ADD : EPI_NONE, d->act, M, N, T, a, b, c, nullptr, acc ? c : nullptr, nullptr, ws);
+    launch_weight_grad(dt, acc, M, N, T, a, b, c, splitk_ws, ws);
   };
   auto colsum = [&](const void* a, int N, void* out, hipStream_t s) {
     float* part = s == st ? pcol2 : pcol;   // per stream, so that the two sums may run at the same time
@@ -490,6 +501,33 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
   if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
   launch_gemm(dtype, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
               (hipStream_t)stream);
+  return finish();
+}
+
+static int check_weight_grad_shape(int dtype, int64_t M, int64_t N, int64_t K) {
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
+  if (M <= 0 || N <= 0 || K <= 0) return SLAPO_ERR_SHAPE;
+  if (M * N >= ((int64_t)1 << 31) || M * K >= ((int64_t)1 << 31) || N * K >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  if (M % 8 || N % 8) return SLAPO_ERR_ALIGN;
+  return SLAPO_OK;
+}
+
+int slapo_weight_grad_workspace(int dtype, int64_t M, int64_t N, int64_t K, size_t* ws_bytes) {
+  if (!ws_bytes) return SLAPO_ERR_NULL;
+  const int rc = check_weight_grad_shape(dtype, M, N, K);
+  if (rc) return rc;
+  *ws_bytes = weight_grad_ws_bytes(dtype, (int)M, (int)N, (int)K);
+  return SLAPO_OK;
+}
+
+int slapo_weight_grad(int dtype, int accumulate, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+                      void* ws, void* stream) {
+  const int rc = check_weight_grad_shape(dtype, M, N, K);
+  if (rc) return rc;
+  if (!A || !B || !C) return SLAPO_ERR_NULL;
+  if (!ws && weight_grad_ws_bytes(dtype, (int)M, (int)N, (int)K)) return SLAPO_ERR_NULL;
+  if (misaligned(A) || misaligned(B) || misaligned(C) || misaligned(ws)) return SLAPO_ERR_ALIGN;
+  launch_weight_grad(dtype, accumulate ? 1 : 0, (int)M, (int)N, (int)K, A, B, C, (float*)ws, (hipStream_t)stream);
   return finish();
 }
 

@@ -9,6 +9,7 @@
 // strided one (the "N" operand of dY*W and both operands of dY^T*X) stay in their memory order in LDS and
 // are read with the transposing ds_read_b64_tr_b16, so no transposed copy of any tensor is ever made.
 // fp32 path: a plain LDS-tiled FMA kernel (correctness mode).
+#include <stdlib.h>
 #include <type_traits>
 
 #include "common.h"
@@ -181,9 +182,16 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   // and every A (B) slab that reaches the L2 is used by all tiles of its row (column) in the block.
   const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
   const int nblk = tiles_m * tiles_n;
+  // Split-K instances: `act` K ranges per tile, every (range, tile) pair a workgroup; consecutive ids walk the
+  // tiles of one range, so the blocks an XCD holds still share operand panels.
+  constexpr bool SPLITK = (EPI == EPI_SPLITK);
+  static_assert(!SPLITK || NS > 0, "split-K instances use the direct-load pipeline");
+  const int splits = SPLITK ? act : 1;
   int bid = blockIdx.x;
-  const int per_xcd = nblk / 8;
+  const int per_xcd = (nblk * splits) / 8;
   if (bid < per_xcd * 8) bid = (bid & 7) * per_xcd + (bid >> 3);
+  const int split = SPLITK ? bid / nblk : 0;
+  if (SPLITK) bid -= split * nblk;
   constexpr int GROUP_M = 4;
   const int group = bid / (GROUP_M * tiles_n);
   const int first_m = group * GROUP_M;
@@ -233,7 +241,11 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   }
   const int64_t stepA = A_KC ? BK : (int64_t)BK * lda, stepB = B_KC ? BK : (int64_t)BK * ldb;
 
-  const int nk = (K + BK - 1) / BK;
+  // slabs of this workgroup: all of them, or the split's range (the host makes every range non-empty)
+  const int nk_all = (K + BK - 1) / BK;
+  const int nk_per = (nk_all + splits - 1) / splits;
+  const int ks0 = SPLITK ? split * nk_per : 0;
+  const int nk = SPLITK ? (nk_all - ks0 < nk_per ? nk_all - ks0 : nk_per) : nk_all;
   static_assert(PF == 1 || PF == 2, "register prefetch depth");
   u32x4_t ra0[A_LOADS], rb0[B_LOADS], ra1[A_LOADS], rb1[B_LOADS];   // register sets: slab k lives in set k % PF
   // Every call issues exactly A_LOADS + B_LOADS loads (slab index clamped to the last one), so the number
@@ -295,7 +307,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   auto load_direct = [&](int kstep, int stage) {
     bf16_t* a = sA + stage * SA + lw * 512;
     bf16_t* b = sB + stage * SB + lw * 512;
-    const unsigned soa = (unsigned)kstep * (unsigned)(stepA * 2), sob = (unsigned)kstep * (unsigned)(stepB * 2);
+    const unsigned soa = (unsigned)(ks0 + kstep) * (unsigned)(stepA * 2), sob = (unsigned)(ks0 + kstep) * (unsigned)(stepB * 2);
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) buffer_load_lds_16(base_a, bytes_a, a + i * NTHR * 8, voa[i], soa);
 #pragma unroll
@@ -612,7 +624,12 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
           store8h<F16>(q, o0);
           store8h<F16>(q + 8, o1);
         }
-        if (EPI != EPI_GATE && EPI != EPI_DGATE) store8h<F16>(C + idx, v);
+        else if (EPI == EPI_SPLITK) {
+          float* part = reinterpret_cast<float*>(aux_out) + (int64_t)split * M * N + idx;
+          *reinterpret_cast<float4*>(part) = make_float4(v[0], v[1], v[2], v[3]);
+          *reinterpret_cast<float4*>(part + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        }
+        if (EPI != EPI_GATE && EPI != EPI_DGATE && EPI != EPI_SPLITK) store8h<F16>(C + idx, v);
       }
     }
   }
@@ -750,6 +767,83 @@ static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, co
     launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, 0, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else
     launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+}
+
+// ---- weight gradients with few output tiles: several K ranges per tile ---------------------------------
+// C (+)= sum over the ranges of the fp32 partial tiles, added in range order (so the result does not depend on
+// which workgroup finished first), eight columns per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(int64_t chunks, int64_t mn, int splits,
+                                                            const float* __restrict__ ws, T* C, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    float v[8];
+    load8(ws + (int64_t)s * mn + i * 8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+  if (accumulate) {
+    float v[8];
+    load8(C + i * 8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+  store8(C + i * 8, acc);
+}
+
+// Number of K ranges for a weight gradient: 1 (plain GEMM) unless the 128x128 tiles leave most of the chip idle
+// and K is long; then as many as bring the grid to about one workgroup per CU, each range at least 48 slabs
+// (measured: at M = N = 1024 four ranges take 41 us against 70 us at K = 16384, but 22.5 against 20.4 at K = 4096,
+// where the second kernel and the partial tiles cost more than the idle CUs).
+static int weight_grad_splits(int M, int N, int K) {
+  static const bool disabled = getenv("SLAPO_NO_SPLITK") && atoi(getenv("SLAPO_NO_SPLITK")) != 0;   // A/B timing
+  if (disabled || K % 256 != 0 || N % 8 != 0) return 1;
+  const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+  if (t128 >= 160) return 1;
+  int64_t s = 256 / t128;
+  const int64_t by_len = (K / 64) / 48;
+  if (s > by_len) s = by_len;
+  if (s > 8) s = 8;
+  return s < 2 ? 1 : (int)s;
+}
+
+size_t weight_grad_ws_bytes(int dtype, int M, int N, int K) {
+  const int s = dtype == DT_FP32 ? 1 : weight_grad_splits(M, N, K);
+  return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
+}
+
+void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
+                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st);
+
+template <bool F16>
+static void launch_splitk(int splits, int accumulate, int M, int N, int K, const void* A, const void* B, void* C,
+                          float* ws, hipStream_t st) {
+  constexpr int BM = 128, BN = 128;
+  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const size_t lds = gemm_lds_bytes<BM, BN, 64, 2, 2, 2, 4>();
+  auto kern = gemm_bf16_kernel<GEMM_TN, BM, BN, 64, 2, 2, 2, 2, 4, 4, false, EPI_SPLITK, F16>;
+  (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3((2 * 2 * 2 + 4) * 64), lds, st, M, N, K, (const bf16_t*)A,
+                     (const bf16_t*)B, (bf16_t*)C, (const bf16_t*)nullptr, (const bf16_t*)nullptr,
+                     reinterpret_cast<bf16_t*>(ws), splits);
+  const int64_t mn = (int64_t)M * N, chunks = mn / 8;
+  const dim3 grid((unsigned)((chunks + 255) / 256));
+  if (F16) hipLaunchKernelGGL(splitk_reduce_kernel<f16_t>, grid, dim3(256), 0, st, chunks, mn, splits, ws, (f16_t*)C, accumulate);
+  else hipLaunchKernelGGL(splitk_reduce_kernel<bf16_t>, grid, dim3(256), 0, st, chunks, mn, splits, ws, (bf16_t*)C, accumulate);
+}
+
+void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const void* A, const void* B, void* C,
+                        float* ws, hipStream_t st) {
+  const int splits = (ws && dtype != DT_FP32) ? weight_grad_splits(M, N, K) : 1;
+  if (splits == 1) {
+    launch_gemm(dtype, GEMM_TN, accumulate ? EPI_ADD : EPI_NONE, 0, M, N, K, A, B, C, nullptr, accumulate ? C : nullptr,
+                nullptr, st);
+    return;
+  }
+  if (dtype == DT_FP16) launch_splitk<true>(splits, accumulate, M, N, K, A, B, C, ws, st);
+  else launch_splitk<false>(splits, accumulate, M, N, K, A, B, C, ws, st);
 }
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,

@@ -10,10 +10,18 @@ enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
 // EPI_GATE: the product's columns are (gate, up) pairs; C [M,N/2] = silu(gate) * up, aux_out [M,N] = the pair
 //   (up * silu'(gate), silu(gate)), the two factors backward multiplies the gradient of C with.
 // EPI_DGATE: the product is that gradient [M,N]; C [M,2N] = (acc * aux_in[m,2n], acc * aux_in[m,2n+1]).
-enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_ACT = 2, EPI_DACT = 3, EPI_ADD = 4, EPI_GATE = 5, EPI_DGATE = 6 };
+// EPI_SPLITK (internal to the weight-gradient path): the workgroup covers one of `act` K ranges of its tile and
+//   writes the fp32 accumulators to aux_out (a float workspace [splits][M][N]); splitk_reduce sums them.
+enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_ACT = 2, EPI_DACT = 3, EPI_ADD = 4, EPI_GATE = 5, EPI_DGATE = 6, EPI_SPLITK = 7 };
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
                  void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st);
+// Weight gradient C[M,N] (+)= A[K,M]^T B[K,N] (accumulate: add to C). Outputs with too few tiles to fill the
+// chip are computed in several K ranges at once (fp32 partial tiles in `ws`, summed in range order by a second
+// kernel: deterministic); weight_grad_ws_bytes says how much workspace a shape wants (0: none, plain GEMM).
+size_t weight_grad_ws_bytes(int dtype, int M, int N, int K);
+void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const void* A, const void* B, void* C,
+                        float* ws, hipStream_t st);
 
 struct AttnShape {
   int batch, seq, hidden, heads, causal;

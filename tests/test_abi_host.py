@@ -140,3 +140,17 @@ def test_attention_width_other_than_hidden():
         with pytest.raises(B.SlapoError) as e:
             B.slapo_layer_workspace(B.make_desc(**dict(base, **kw)))
         assert e.value.status == code, (kw, e.value.status)
+
+
+def test_weight_gradient_workspace_rule():
+    assert B.slapo_weight_grad_workspace(B.BF16, 1024, 1024, 16384) == 4 * 1024 * 1024 * 4     # 64 tiles -> 4 K ranges
+    assert B.slapo_weight_grad_workspace(B.BF16, 1024, 1024, 8192) == 2 * 1024 * 1024 * 4      # ranges of at least 48 slabs
+    assert B.slapo_weight_grad_workspace(B.BF16, 1024, 1024, 4096) == 0                         # too short to cut up
+    assert B.slapo_weight_grad_workspace(B.BF16, 128, 128, 65536) == 8 * 128 * 128 * 4          # never more than 8
+    assert B.slapo_weight_grad_workspace(B.BF16, 1024, 4096, 4096) == 0                         # a full round of tiles
+    assert B.slapo_weight_grad_workspace(B.BF16, 1024, 1024, 4000) == 0                         # K no multiple of 256
+    assert B.slapo_weight_grad_workspace(B.FP32, 1024, 1024, 4096) == 0
+    lib = B.lib()
+    assert lib.slapo_weight_grad(0, 0, 1024, 1024, 16384, 4096, 4096, 4096, None, None) == -1   # wants a workspace
+    assert lib.slapo_weight_grad(0, 0, 1024, 1028, 16384, 4096, 4096, 4096, 4096, None) == -4
+    assert lib.slapo_weight_grad(0, 0, 0, 1024, 4096, 4096, 4096, 4096, 4096, None) == -2

@@ -72,3 +72,34 @@ def test_gemm_epilogues(dtype, act):
     C2 = auxd.clone()                          # in-place accumulate (aux_in aliases C)
     B.slapo_gemm(dtype, B.NT, B.EPI_ADD, act, M, N, K, A, Wt, C2, aux_in=C2)
     assert err(C2, acc + aux) <= tol
+
+
+# (M, N, K): tile-starved weight gradients that take the several-K-ranges path (4, 2 and 8 ranges, ragged edges),
+# and two that must not (K too short to cut up, enough tiles)
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP16, W.FP32])
+@pytest.mark.parametrize("M,N,K,split", [(1024, 1024, 16384, True), (136, 264, 8192, True), (264, 136, 24576, True),
+                                         (1024, 1024, 4096, False), (2048, 1536, 1024, False)])
+def test_weight_gradient_in_k_ranges(dtype, M, N, K, split):
+    rng = np.random.default_rng(M + K)
+    a = store(rng.standard_normal((K, M)), dtype)
+    b = store(rng.standard_normal((K, N)) * 0.05, dtype)
+    c0 = store(rng.standard_normal((M, N)), dtype)
+    ref = a.astype(np.float64).T @ b.astype(np.float64)
+    nbytes = B.slapo_weight_grad_workspace(dtype, M, N, K)
+    assert (nbytes > 0) == (split and dtype != W.FP32)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=DEV)
+    A, Bt = to_dev(a, dtype), to_dev(b, dtype)
+    out = torch.empty(M, N, dtype=A.dtype, device=DEV)
+    B.slapo_weight_grad(dtype, 0, M, N, K, A, Bt, out, ws)
+    tol = TOL[dtype]
+    assert err(out, ref) <= tol
+    ws.fill_(0x7F)                                   # stale workspace contents must not matter
+    out2 = torch.empty_like(out)
+    B.slapo_weight_grad(dtype, 0, M, N, K, A, Bt, out2, ws)
+    assert torch.equal(out, out2)                    # bit for bit, whichever workgroup finishes first
+    acc = to_dev(c0, dtype)
+    B.slapo_weight_grad(dtype, 1, M, N, K, A, Bt, acc, ws)
+    assert err(acc, ref + c0) <= tol
+    plain = torch.empty_like(out)                    # the one-range kernel: same product, other summation order
+    B.slapo_gemm(dtype, B.TN, B.EPI_NONE, 0, M, N, K, A, Bt, plain)
+    assert err(plain, to_np(out)) <= tol
