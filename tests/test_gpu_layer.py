@@ -147,3 +147,22 @@ def test_layer_parity_full_size(key):
     tol = TOL[cfg.dtype]
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, (bad, errs)
+
+
+DEGENERATE = [
+    # one token, one head, the narrowest FFN the alignment rules allow
+    W.LayerConfig("one-token-fp32", 1, 1, 64, 1, 8, causal=0, dropout_p=0.1, dtype=W.FP32, config_id=31),
+    W.LayerConfig("one-token-bf16-preln-causal", 1, 1, 64, 1, 8, causal=1, dropout_p=0.0, dtype=W.BF16, pre_ln=1, config_id=32),
+    # a few tokens, sequences down to a single visible key
+    W.LayerConfig("five-tokens-bf16-preln-causal", 3, 5, 128, 2, 24, causal=1, dropout_p=0.1, dtype=W.BF16, pre_ln=1,
+                  len_lo=1, len_hi=5, config_id=33),
+    W.LayerConfig("five-tokens-fp32-d128", 2, 5, 128, 1, 24, causal=0, dropout_p=0.2, dtype=W.FP32, len_lo=1, len_hi=2, config_id=34),
+]
+
+
+@pytest.mark.parametrize("cfg", DEGENERATE, ids=lambda c: c.name)
+def test_layer_parity_degenerate_sizes(cfg):
+    errs, _, _ = run_case(cfg)
+    tol = TOL[cfg.dtype]
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)

@@ -183,3 +183,15 @@ def test_llama_layer_parity_full_size():
     errs, _, _ = run_case(cfg, perturbed=False, check_saved=False)
     bad = {k: v for k, v in errs.items() if not v <= TOL[cfg.dtype]}
     assert not bad, (bad, errs)
+
+
+@pytest.mark.parametrize("cfg", [
+    W.LayerConfig("llama-one-token-fp32", 1, 1, 64, 1, 8, causal=1, dropout_p=0.0, dtype=W.FP32, pre_ln=1, ln_eps=1e-6,
+                  arch=W.LLAMA, config_id=41),
+    W.LayerConfig("llama-three-tokens-bf16", 2, 3, 128, 1, 8, causal=1, dropout_p=0.1, dtype=W.BF16, pre_ln=1, ln_eps=1e-6,
+                  arch=W.LLAMA, len_lo=1, len_hi=3, config_id=42),
+], ids=lambda c: c.name)
+def test_llama_layer_parity_degenerate_sizes(cfg):
+    errs, _, _ = run_case(cfg)
+    bad = {k: v for k, v in errs.items() if not v <= TOL[cfg.dtype]}
+    assert not bad, (bad, errs)
