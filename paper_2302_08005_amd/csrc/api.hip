@@ -263,22 +263,22 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
     // no biases; queries and keys are rotated in place by their position before the attention reads them
     float* table = (float*)(sc + W.rope);
     launch_rope_table(d->seq, A / d->heads, d->rope_base, table, st);
-    launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, 3 * A, H, attn_in, p->wqkv, qkv, nullptr, nullptr, nullptr, st);
+    launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, 3 * A, H, attn_in, p->wqkv, qkv, nullptr, nullptr, nullptr, st, true);
     launch_rope(dt, T, d->seq, A, A / d->heads, table, qkv, 0, st);
   } else {
-    launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * A, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st);
+    launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * A, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st, true);
   }
   launch_attn_fwd(dt, as, qkv, seqlens, attn, lse, st);
-  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, A, attn, p->wo, r, nullptr, nullptr, nullptr, st);
+  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, A, attn, p->wo, r, nullptr, nullptr, nullptr, st, true);
   const void* bo = llama ? nullptr : p->bo;
   const void* b2 = llama ? nullptr : p->b2;
   if (d->pre_ln) launch_bdrln_fwd(dt, T, H, r, bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, rms, st);
   else launch_bdrln_fwd(dt, T, H, r, bo, x, p->ln1_g, p->ln1_b, z1, y1, mu1, rstd1, dp0, d->ln_eps, rms, st);
   if (llama)   // w1 holds (gate, up) row pairs: one product, gated in the epilogue; `u` keeps the backward factors
-    launch_gemm(dt, GEMM_NT, EPI_GATE, d->act, T, 2 * F, H, y1, p->w1, g, nullptr, nullptr, u, st);
+    launch_gemm(dt, GEMM_NT, EPI_GATE, d->act, T, 2 * F, H, y1, p->w1, g, nullptr, nullptr, u, st, true);
   else
-    launch_gemm(dt, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st);
-  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st);
+    launch_gemm(dt, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st, true);
+  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st, true);
   if (d->pre_ln) {
     launch_bdrln_fwd(dt, T, H, r, b2, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, dp1, d->ln_eps, rms, st);
   } else {
@@ -500,7 +500,7 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
   if (layout == GEMM_NT && (K % 8)) return SLAPO_ERR_ALIGN;
   if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
   launch_gemm(dtype, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
-              (hipStream_t)stream);
+              (hipStream_t)stream, true);
   return finish();
 }
 

@@ -747,10 +747,23 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 // tail).
 template <int LAYOUT, bool F16>
 static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
-                        const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
+                        const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo) {
   const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
-  if (K % 128 == 0 && t256 >= 192)
+  // A grid of 256x256 tiles runs in rounds of 256 (one workgroup per CU) and a thin last round costs a full one:
+  // 320 tiles take two rounds for 1.25 rounds of work. A GEMM that has the chip to itself (`solo`: the forward
+  // pass, the exported building block) therefore takes 128x128 tiles when their round count is the cheaper one,
+  // at the long-K rates of the two kernels (PFLOP/s: 1.30 / 1.17 / 1.10 for NT / NN / TN against 1.05 / 1.0 /
+  // 1.0; a 256x256 tile is four small ones). In the backward pass the idle CUs of a thin round are exactly where
+  // the other stream's kernels run, and the same rule makes the step slower (2.7B-shaped layer: 5.39 ms against
+  // 4.99 ms; on a single stream 5.06 against 5.62), so it is not applied there.
+  bool big = K % 128 == 0 && t256 >= 192;
+  if (solo && big && K % 256 == 0 && K >= 2048) {
+    const double e256 = LAYOUT == GEMM_NT ? 1.30 : LAYOUT == GEMM_NN ? 1.17 : 1.10, e128 = LAYOUT == GEMM_NT ? 1.05 : 1.0;
+    const double c256 = (double)((t256 + 255) / 256) * 4.0 / e256, c128 = (double)((t128 + 255) / 256) / e128;
+    big = c256 <= c128;
+  }
+  if (big)
     launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
   else if (K % 256 == 0 && t128 >= 160 && LAYOUT == GEMM_TN)
     // both operands go through the transposing LDS reads (two per fragment): the 64x64 wave tile of the
@@ -814,9 +827,6 @@ size_t weight_grad_ws_bytes(int dtype, int M, int N, int K) {
   return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
 }
 
-void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
-                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st);
-
 template <bool F16>
 static void launch_splitk(int splits, int accumulate, int M, int N, int K, const void* A, const void* B, void* C,
                           float* ws, hipStream_t st) {
@@ -847,7 +857,7 @@ void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const vo
 }
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
-                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st) {
+                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo) {
   if (dtype == DT_FP32) {
     dim3 grid((N + 63) / 64, (M + 63) / 64);
 #define SLAPO_F32(L)                                                                                      \
@@ -860,9 +870,9 @@ void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, c
     return;
   }
 #define SLAPO_H(F)                                                                                          \
-  if (layout == GEMM_NT) launch_bf16<GEMM_NT, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);     \
-  else if (layout == GEMM_NN) launch_bf16<GEMM_NN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); \
-  else launch_bf16<GEMM_TN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st)
+  if (layout == GEMM_NT) launch_bf16<GEMM_NT, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo);     \
+  else if (layout == GEMM_NN) launch_bf16<GEMM_NN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo); \
+  else launch_bf16<GEMM_TN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo)
   if (dtype == DT_FP16) { SLAPO_H(true); } else { SLAPO_H(false); }
 #undef SLAPO_H
 }
