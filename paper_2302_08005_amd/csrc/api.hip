@@ -337,6 +337,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   const int nrow = bdrln_bwd_blocks(T), ncol = colsum_blocks(T);
   // `st` carries the data-gradient chain; `ws` the weight / bias gradients that hang off it
   SideStream* side = side_stream();
+  const bool solo = side == nullptr;   // one stream: every GEMM has the chip to itself
   hipStream_t ws = side ? side->stream : st;
   auto fork = [&](int i) {   // everything issued on st so far happens before what follows on ws
     if (side) { (void)hipEventRecord(side->fork[i], st); (void)hipStreamWaitEvent(ws, side->fork[i], 0); }
@@ -344,7 +345,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   // weight gradient: C (+)= A^T B
   float* splitk_ws = W.splitk ? (float*)(sc + W.splitk) : nullptr;
   auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
-    launch_weight_grad(dt, acc, M, N, T, a, b, c, splitk_ws, ws);
+    launch_weight_grad(dt, acc, M, N, T, a, b, c, splitk_ws, ws, solo);
   };
   auto colsum = [&](const void* a, int N, void* out, hipStream_t s) {
     float* part = s == st ? pcol2 : pcol;   // per stream, so that the two sums may run at the same time
@@ -374,17 +375,17 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   dweight(H, F, t1, g, gr->w2);
   if (llama) {
     // dG = dR2 W2, turned into the (gate, up) gradient pairs [T,2F] by the two saved factors in the epilogue
-    launch_gemm(dt, GEMM_NN, EPI_DGATE, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+    launch_gemm(dt, GEMM_NN, EPI_DGATE, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st, solo);
     fork(1);
     dweight(2 * F, H, du, y1, gr->w1);
-    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 2 * F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
+    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 2 * F, du, p->w1, t0, nullptr, nullptr, nullptr, st, solo);
   } else {
-    launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st);
+    launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st, solo);
     fork(1);
     colsum(du, F, gr->b1, ws);
     dweight(F, H, du, y1, gr->w1);
-    if (d->pre_ln) launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st);
-    else launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st);
+    if (d->pre_ln) launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st, solo);
+    else launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st, solo);
   }
   // ---- attention block ----
   if (d->pre_ln) {
@@ -396,7 +397,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   }
   fork(2);
   dweight(H, A, t3, attn, gr->wo);
-  launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, A, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st);
+  launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, A, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st, solo);
   launch_attn_bwd(dt, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
   if (llama) {
     // the attention gradients are w.r.t. the rotated queries and keys: turn them back (the rotation's transpose)
@@ -407,12 +408,12 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   fork(3);
   if (d->pre_ln) {
     dweight(3 * A, H, dqkv, sv + L.n1, gr->wqkv);
-    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * A, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st);
+    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * A, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st, solo);
     launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, rms, st);
     reduce_rows(gr->ln1_g, g_ln1_b, nullptr);
   } else {
     dweight(3 * A, H, dqkv, x, gr->wqkv);
-    launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * A, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st);
+    launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * A, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st, solo);
   }
   // the last bias gradient goes behind the data gradient on the caller's stream: the helper stream's last
   // product is the longer one, and this way the two streams end at about the same time

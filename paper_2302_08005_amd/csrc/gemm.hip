@@ -845,11 +845,11 @@ static void launch_splitk(int splits, int accumulate, int M, int N, int K, const
 }
 
 void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const void* A, const void* B, void* C,
-                        float* ws, hipStream_t st) {
+                        float* ws, hipStream_t st, bool solo) {
   const int splits = (ws && dtype != DT_FP32) ? weight_grad_splits(M, N, K) : 1;
   if (splits == 1) {
     launch_gemm(dtype, GEMM_TN, accumulate ? EPI_ADD : EPI_NONE, 0, M, N, K, A, B, C, nullptr, accumulate ? C : nullptr,
-                nullptr, st);
+                nullptr, st, solo);
     return;
   }
   if (dtype == DT_FP16) launch_splitk<true>(splits, accumulate, M, N, K, A, B, C, ws, st);

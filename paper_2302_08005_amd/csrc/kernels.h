@@ -22,7 +22,7 @@ void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, c
 // kernel: deterministic); weight_grad_ws_bytes says how much workspace a shape wants (0: none, plain GEMM).
 size_t weight_grad_ws_bytes(int dtype, int M, int N, int K);
 void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const void* A, const void* B, void* C,
-                        float* ws, hipStream_t st);
+                        float* ws, hipStream_t st, bool solo = false);
 
 struct AttnShape {
   int batch, seq, hidden, heads, causal;
