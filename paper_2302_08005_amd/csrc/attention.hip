@@ -73,26 +73,33 @@ __device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + 
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
-// 64 x D tile: global rows (clamped to `last_row`, so every load is unconditional) -> registers -> LDS.
-// Rows past the end of the sequence are never zeroed: the kernels mask the scores that involve them.
+// A 64 x D tile is brought in by direct global -> LDS loads (no staging registers, no ds_write). One
+// wave-level load fills 1 KB of consecutive LDS, lane l at byte 16 l, so the 16-byte padding at the end of every
+// tile row is simply one more slot: the tile is 64 * (D/8 + 1) slots = D/8 + 1 wave-level loads, and the lane
+// that lands on a padding slot fetches the row's first piece again (nobody reads the padding). The loads of
+// a tile are dealt out to the four wavefronts round-robin. Rows past the end of the sequence are whatever
+// follows in memory (the next sample's rows, zero past the end of the tensor: the buffer bounds): finite
+// values that only ever meet masked scores.
 template <int D>
-struct TileRegs {
-  static constexpr int N = 64 * D / 8 / 256;
-  u32x4_t r[N];
-  __device__ __forceinline__ void load(const bf16_t* src, int64_t row_stride, int row0, int last_row, int tid) {
+struct TileDirect {
+  static constexpr int SPR = D / 8 + 1;            // 16-byte slots per padded row = wave-level loads per tile
+  static constexpr int MINE = (SPR + 3) / 4;       // loads per tile of one wavefront (at most)
+  unsigned voff[MINE];
+  int wave;                                        // wave-uniform
+  __device__ __forceinline__ void init(int lane, int wave_uniform, unsigned row_stride_bytes) {
+    wave = wave_uniform;
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int q = tid + i * 256, row = q / (D / 8), c = q % (D / 8);
-      int gr = row0 + row;
-      gr = gr > last_row ? last_row : gr;
-      r[i] = *reinterpret_cast<const u32x4_t*>(src + (int64_t)gr * row_stride + c * 8);
+    for (int k = 0; k < MINE; ++k) {
+      const int slot = (wave + 4 * k) * 64 + lane, row = slot / SPR, pos = slot % SPR;
+      voff[k] = (unsigned)row * row_stride_bytes + (unsigned)(pos == D / 8 ? 0 : pos) * 16u;
     }
   }
-  __device__ __forceinline__ void store(bf16_t* tile, int tid) const {
+  // tile rows row0.. of the operand that starts at `base` (`bytes` long from there) -> LDS tile
+  __device__ __forceinline__ void issue(const bf16_t* base, unsigned bytes, bf16_t* tile, unsigned row0_bytes) const {
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int q = tid + i * 256, row = q / (D / 8), c = q % (D / 8);
-      *reinterpret_cast<u32x4_t*>(tile + row * Tile<D>::P + c * 8) = r[i];
+    for (int k = 0; k < MINE; ++k) {
+      const int instr = wave + 4 * k;
+      if (instr < SPR) buffer_load_lds_16(base, bytes, tile + instr * 512, voff[k], row0_bytes);
     }
   }
 };
@@ -180,32 +187,6 @@ __device__ __forceinline__ uint32_t keep16_key_lane(const DropoutParams& dp, uin
   return bits;
 }
 
-// Tile pipeline shared by the three kernels: tile t is computed from LDS stage t&1 while the loads of
-// tiles t+1 and t+2 are in flight in two register sets. Loads and stores are issued on every step with a
-// clamped tile index (the surplus ones land in a stage nobody reads), so the number of loads in flight is
-// the same on every path and the wait before an LDS store covers the oldest tile only.
-#define SLAPO_TILE_PIPELINE(n_tiles, LOAD, STORE, COMPUTE)        \
-  do {                                                            \
-    if ((n_tiles) > 0) {                                          \
-      const int last_ = (n_tiles)-1;                              \
-      LOAD(0, 0);                                                 \
-      LOAD(1, (1 < last_ ? 1 : last_));                           \
-      STORE(0, 0);                                                \
-      __syncthreads();                                            \
-      for (int it_ = 0; it_ < (n_tiles); it_ += 2) {              \
-        LOAD(0, (it_ + 2 < last_ ? it_ + 2 : last_));             \
-        COMPUTE(0, it_);                                          \
-        STORE(1, 1);                                              \
-        __syncthreads();                                          \
-        if (it_ + 1 >= (n_tiles)) break;                          \
-        LOAD(1, (it_ + 3 < last_ ? it_ + 3 : last_));             \
-        COMPUTE(1, it_ + 1);                                      \
-        STORE(0, 0);                                              \
-        __syncthreads();                                          \
-      }                                                           \
-    }                                                             \
-  } while (0)
-
 // =================================== forward =====================================================
 template <int D, bool DROP, bool F16>
 __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
@@ -242,9 +223,18 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
   float m = -INFINITY, l = 0.f;   // running maximum (raw score units) and sum of this lane's half row
   const uint64_t row_blk = ((((uint64_t)b * sh.heads + a) * S + (uint64_t)q_ld) * (uint64_t)S) >> 3;   // DROP: block of key 0
 
-  TileRegs<D> rk[2], rv[2];
-#define FWD_LOAD(set, t) do { rk[set].load(base + H, rs, (t) * 64, S - 1, tid); rv[set].load(base + 2 * H, rs, (t) * 64, S - 1, tid); } while (0)
-#define FWD_STORE(stage, set) do { rk[set].store(smem + (stage) * 2 * TE, tid); rv[set].store(smem + (stage) * 2 * TE + TE, tid); } while (0)
+  // K and V tiles of 64 keys: direct loads into two LDS stages, tile t+1 on its way while tile t is computed
+  TileDirect<D> td;
+  td.init(lane, __builtin_amdgcn_readfirstlane(wave), (unsigned)(rs * 2));
+  const bf16_t* kbase = base + H;
+  const bf16_t* vbase = base + 2 * H;
+  const int64_t total_elems = (int64_t)sh.batch * S * rs;
+  const unsigned kbytes = (unsigned)((total_elems - (kbase - qkv)) * 2), vbytes = (unsigned)((total_elems - (vbase - qkv)) * 2);
+  auto issue_tile = [&](int stage, int t) {
+    const unsigned row0_bytes = (unsigned)t * 64u * (unsigned)(rs * 2);
+    td.issue(kbase, kbytes, smem + stage * 2 * TE, row0_bytes);
+    td.issue(vbase, vbytes, smem + stage * 2 * TE + TE, row0_bytes);
+  };
   auto compute = [&](int stage, int it) {
     const int kv0 = it * 64;
     if (sh.causal && kv0 > wave_q_max) return;   // every key of the tile lies in this wave's future
@@ -313,9 +303,15 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
           o[t] = mfma16<F16>(frag_tr<D>(vt, ft_base, i * 32 + 16 * h, t), pf, o[t]);
       }
   };
-  SLAPO_TILE_PIPELINE(n_tiles, FWD_LOAD, FWD_STORE, compute);
-#undef FWD_LOAD
-#undef FWD_STORE
+  if (n_tiles > 0) {
+    issue_tile(0, 0);
+    __syncthreads();   // (waits for this wavefront's loads, then for everybody's)
+    for (int it = 0; it < n_tiles; ++it) {
+      if (it + 1 < n_tiles) issue_tile((it + 1) & 1, it + 1);   // that stage was last read before the barrier above
+      compute(it & 1, it);
+      __syncthreads();
+    }
+  }
 
   const float l_tot = l + __shfl_xor(l, 32, 64);
   const float inv = l_tot > 0.f ? (DROP ? sh.drop.scale : 1.f) / l_tot : 0.f;
@@ -414,12 +410,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
 
   const int q_first = sh.causal ? (kv_base / 64) : 0;
   const int n_tiles = (kv_base < kv_len) ? (S + 63) / 64 - q_first : 0;  // nothing to do for fully hidden keys
-  TileRegs<D> rq[2], rd[2];
-  float aux[2] = {0.f, 0.f};
   const int stat_row = tid & 63;
   // threads 0..63 carry lse, threads 64..127 delta, threads 128..255 duplicate them (same values to the same
-  // slots, so no thread is special). The value is only touched when it is stored to LDS a step later, so
-  // the load stays in flight like the tile loads.
+  // slots, so no thread is special). The value is only touched when it is stored to LDS after the step's
+  // compute, so the load stays in flight like the tile loads.
   const float* stat_src = (tid & 127) < 64 ? lse_row : delta_row;
   const float stat_mul = (tid & 127) < 64 ? LOG2E : 1.0f;
   auto load_stats = [&](int q0) -> float {
@@ -427,8 +421,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
     q = q < S ? q : S - 1;
     return stat_src[q];
   };
-#define DKV_LOAD(set, t) do { const int q0_ = (q_first + (t)) * 64; rq[set].load(base, rs, q0_, S - 1, tid); rd[set].load(dobase, H, q0_, S - 1, tid); aux[set] = load_stats(q0_); } while (0)
-#define DKV_STORE(stage, set) do { bf16_t* t0_ = smem + (stage) * STAGE; rq[set].store(t0_, tid); rd[set].store(t0_ + TE, tid); reinterpret_cast<float*>(t0_ + 2 * TE)[tid & 127] = aux[set] * stat_mul; } while (0)
+  // Q and dO tiles of 64 queries: direct loads into two LDS stages, tile t+1 on its way while tile t is computed
+  TileDirect<D> tq, tdo;
+  tq.init(lane, __builtin_amdgcn_readfirstlane(wave), (unsigned)(rs * 2));
+  tdo.init(lane, __builtin_amdgcn_readfirstlane(wave), (unsigned)(H * 2));
+  const unsigned qbytes = (unsigned)(((int64_t)sh.batch * S * rs - (base - qkv)) * 2);
+  const unsigned dbytes = (unsigned)(((int64_t)sh.batch * S * H - (dobase - dout)) * 2);
+  auto issue_tile = [&](int stage, int t) {
+    const unsigned q0 = (unsigned)(q_first + t) * 64u;
+    tq.issue(base, qbytes, smem + stage * STAGE, q0 * (unsigned)(rs * 2));
+    tdo.issue(dobase, dbytes, smem + stage * STAGE + TE, q0 * (unsigned)(H * 2));
+  };
+  auto store_stats = [&](int stage, float v) { reinterpret_cast<float*>(smem + stage * STAGE + 2 * TE)[tid & 127] = v * stat_mul; };
   auto compute = [&](int stage, int it) {
     const int q0 = (q_first + it) * 64;
     const bf16_t* qtile = smem + stage * STAGE;
@@ -492,9 +496,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
       }
     }
   };
-  SLAPO_TILE_PIPELINE(n_tiles, DKV_LOAD, DKV_STORE, compute);
-#undef DKV_LOAD
-#undef DKV_STORE
+  if (n_tiles > 0) {
+    issue_tile(0, 0);
+    store_stats(0, load_stats(q_first * 64));
+    __syncthreads();   // (waits for this wavefront's loads, then for everybody's)
+    for (int it = 0; it < n_tiles; ++it) {
+      const bool more = it + 1 < n_tiles;
+      float next_stat = 0.f;
+      if (more) {   // that stage was last read before the barrier above
+        issue_tile((it + 1) & 1, it + 1);
+        next_stat = load_stats((q_first + it + 1) * 64);
+      }
+      compute(it & 1, it);
+      if (more) store_stats((it + 1) & 1, next_stat);
+      __syncthreads();
+    }
+  }
 
   if (my_kv < S) {
     bf16_t* krow = dqkv + ((int64_t)b * S + my_kv) * rs + H + a * D;
@@ -573,9 +590,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[t][r] = 0.f;
 
-  TileRegs<D> rk[2], rv[2];
-#define DQ_LOAD(set, t) do { rk[set].load(base + H, rs, (t) * 64, S - 1, tid); rv[set].load(base + 2 * H, rs, (t) * 64, S - 1, tid); } while (0)
-#define DQ_STORE(stage, set) do { rk[set].store(smem + (stage) * 2 * TE, tid); rv[set].store(smem + (stage) * 2 * TE + TE, tid); } while (0)
+  // K and V tiles of 64 keys: direct loads into two LDS stages, tile t+1 on its way while tile t is computed
+  TileDirect<D> td;
+  td.init(lane, __builtin_amdgcn_readfirstlane(wave), (unsigned)(rs * 2));
+  const bf16_t* kbase = base + H;
+  const bf16_t* vbase = base + 2 * H;
+  const int64_t total_elems = (int64_t)sh.batch * S * rs;
+  const unsigned kbytes = (unsigned)((total_elems - (kbase - qkv)) * 2), vbytes = (unsigned)((total_elems - (vbase - qkv)) * 2);
+  auto issue_tile = [&](int stage, int t) {
+    const unsigned row0_bytes = (unsigned)t * 64u * (unsigned)(rs * 2);
+    td.issue(kbase, kbytes, smem + stage * 2 * TE, row0_bytes);
+    td.issue(vbase, vbytes, smem + stage * 2 * TE + TE, row0_bytes);
+  };
   auto compute = [&](int stage, int it) {
     const int kv0 = it * 64;
     if (sh.causal && kv0 > wave_q_max) return;
@@ -619,9 +645,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
       }
     }
   };
-  SLAPO_TILE_PIPELINE(n_tiles, DQ_LOAD, DQ_STORE, compute);
-#undef DQ_LOAD
-#undef DQ_STORE
+  if (n_tiles > 0) {
+    issue_tile(0, 0);
+    __syncthreads();   // (waits for this wavefront's loads, then for everybody's)
+    for (int it = 0; it < n_tiles; ++it) {
+      if (it + 1 < n_tiles) issue_tile((it + 1) & 1, it + 1);   // that stage was last read before the barrier above
+      compute(it & 1, it);
+      __syncthreads();
+    }
+  }
 
   if (my_q < S) {
     bf16_t* qrow = dqkv + ((int64_t)b * S + my_q) * rs + a * D;

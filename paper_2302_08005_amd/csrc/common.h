@@ -123,6 +123,16 @@ __device__ __forceinline__ void from_f32(bf16_t& d, float f) { d = f32_to_bf16(f
 __device__ __forceinline__ void from_f32(f16_t& d, float f) { d = (f16_t)f; }
 __device__ __forceinline__ void from_f32(float& d, float f) { d = f; }
 
+// One direct 16-byte-per-lane load: lane l of the wavefront fetches base[voffset_l + soffset ..] (bytes; zero
+// beyond `bytes`) into LDS at lds + 16 l. A plain function on purpose: the buffer builtins are only known
+// to the device pass, and a kernel template that names them directly loses its host-side launch stub.
+__device__ __forceinline__ void buffer_load_lds_16(const void* base, unsigned bytes, void* lds, unsigned voffset,
+                                                   unsigned soffset) {
+  // raw buffer resource: stride 0, size in bytes, untyped 32-bit data format; loop-invariant scalars
+  const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds, 16, voffset, soffset, 0, 0);
+}
+
 // Sum over the 64 lanes, returned to every lane. Data-parallel-primitive moves (quad permutes, mirrors inside
 // rows of 16 lanes, then the row broadcasts) keep the whole reduction in the vector ALU: six dependent adds
 // and one lane read instead of six round trips through the LDS crossbar.

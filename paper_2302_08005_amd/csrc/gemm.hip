@@ -103,16 +103,6 @@ __device__ __forceinline__ GateTerms gate_terms(float u, float w) {
 // Why direct loads: a ds_write moves 64 B per clock and keeps the LDS busy meanwhile, so writing a slab
 // costs as much LDS time as reading it three times; measured on the chip, fragment reads running beside
 // register-staged stores take the sum of both times, beside direct loads the maximum.
-// One direct 16-byte-per-lane load: lane l of the wavefront fetches base[voffset_l + soffset ..] (bytes; zero
-// beyond `bytes`) into LDS at lds + 16 l. A plain function on purpose: the buffer builtins are only known
-// to the device pass, and a kernel template that names them directly loses its host-side launch stub.
-__device__ __forceinline__ void buffer_load_lds_16(const void* base, unsigned bytes, void* lds, unsigned voffset,
-                                                   unsigned soffset) {
-  // raw buffer resource: stride 0, size in bytes, untyped 32-bit data format; loop-invariant scalars
-  const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds, 16, voffset, soffset, 0, 0);
-}
-
 template <int N>
 __device__ __forceinline__ void wait_loads_and_lds() {   // at most N vector-memory loads outstanding, LDS ops done
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
