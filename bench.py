@@ -23,7 +23,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (figures and commands in profiles/); None where no counter run has been made.
-TRAFFIC_BYTES_PER_LAUNCH = {"C2-bert-large-layer-bf16": 108.48e6}   # 100.79 MB fetched + 7.69 MB written
+TRAFFIC_BYTES_PER_LAUNCH = {"C2-bert-large-layer-bf16": 108.49e6}   # 100.80 MB fetched + 7.69 MB written
 
 
 def layer_flops(cfg, seqlens):
