@@ -25,8 +25,8 @@
  *   - Return value: SLAPO_OK (0) or a negative slapo_status. Argument checks run before the first
  *     HIP call, so they behave the same on a host without a GPU. Nothing throws or aborts.
  *   - Same inputs and seed give bitwise identical outputs (no floating-point atomics anywhere).
- *   - Element type: SLAPO_BF16 (bf16 storage, fp32 accumulation and fp32 elementwise math) or
- *     SLAPO_FP32 (fp32 everywhere; a correctness mode with simple kernels, not a tuned one).
+ *   - Element type: SLAPO_BF16 or SLAPO_FP16 (16-bit storage, fp32 accumulation and fp32 elementwise math;
+ *     the same kernels) or SLAPO_FP32 (fp32 everywhere; a correctness mode with simple kernels, not a tuned one).
  */
 #ifndef SLAPO_MI355X_H
 #define SLAPO_MI355X_H
@@ -136,7 +136,8 @@ int slapo_layer_fwd(const slapo_layer_desc *desc, const slapo_layer_params *para
                     const int32_t *seqlens, void *y, void *saved, void *scratch, void *stream);
 
 /* Backward: given dy = dL/dy [B,S,H] and the `saved` buffer of the matching forward, writes
- * dx [B,S,H] and the twelve parameter gradients (same shapes and element type as the parameters).
+ * dx [B,S,H] and the parameter gradients (twelve; six for SLAPO_ARCH_LLAMA; same shapes and element type as
+ * the parameters).
  * The dropout masks are regenerated from (seed, layer_id, site, element index), never stored. */
 int slapo_layer_bwd(const slapo_layer_desc *desc, const slapo_layer_params *params, const void *x,
                     const int32_t *seqlens, const void *dy, const void *saved, void *dx,

@@ -5,7 +5,7 @@
 //
 // bf16 path. A workgroup of four wavefronts owns 128 query rows (forward, dQ) or 128 key rows (dK/dV)
 // of one (sample, head); each wavefront owns 32 of them and walks the other sequence dimension in
-// 64-row tiles staged through LDS (two stages, one barrier per tile). All products run on
+// 64-row tiles brought into two LDS stages by direct global -> LDS loads (one barrier per tile). All products run on
 // v_mfma_f32_32x32x16_bf16 and are arranged "transposed" (S^T = K Q^T, O^T = V^T P^T, ...), because
 // then the accumulator layout of the score tile already is the B-operand layout of the next product
 // and the per-row softmax state (max, sum, logsumexp, delta) is one scalar per lane; a row's maximum
