@@ -138,3 +138,37 @@ def test_drift_over_24_bf16_layers_stays_small():
     drift = {"y": err(y, h), "dx": err(dx, g), "worst_grad": worst}
     print("24-layer drift:", drift)
     assert all(v <= 5e-2 for v in drift.values()), drift
+
+
+def test_full_size_24_layer_stack_bottom_and_top_layers():
+    """The 24-layer benchmark stack itself (batch 32, T = 16384), in the launch configuration bench.py times.
+
+    An fp64 oracle chain of 24 such layers would take minutes, so the two ends are checked layer-locally: the
+    bottom layer's output against the oracle applied to x, and the top layer's output and parameter gradients
+    against the oracle applied to the activation the GPU handed that layer (read back, so both sides start
+    from the same stored values) and the injected dy. Everything between is the same kernels on the same shapes.
+    """
+    cfg = W.CONFIGS["C5"]
+    n = cfg.n_layers
+    params = [W.make_params(cfg, layer_id=l) for l in range(n)]
+    x, dy, sl = W.make_inputs(cfg)
+    st = B.Stack(cfg, params)
+    xd, dyd, sld = st.to_device(x), st.to_device(dy), torch.from_numpy(sl).to(DEV)
+    y = st.forward(xd, sld)
+    st.backward(xd, sld, dyd)
+    torch.cuda.synchronize()
+    T, H = cfg.tokens, cfg.hidden
+    acts = st.acts.view(st.dt).view(n - 1, T, H)
+    tol = TOL[cfg.dtype]
+    bottom = L.layer_forward(cfg.replace(layer_id=0), params[0], x, sl)
+    assert err(acts[0].reshape(-1), bottom["y"].reshape(-1)) <= tol
+    del bottom
+    top_in = acts[n - 2].float().cpu().numpy().reshape(cfg.batch, cfg.seq, H)
+    top_cfg = cfg.replace(layer_id=n - 1)
+    c = L.layer_forward(top_cfg, params[n - 1], top_in, sl)
+    g = L.layer_backward(top_cfg, params[n - 1], c, dy)
+    errs = {"y": err(y, c["y"])}
+    for k in W.PARAM_NAMES:
+        errs["d" + k] = err(st.grads[n - 1][k], g[k])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
