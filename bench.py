@@ -289,7 +289,17 @@ def main():
     epi_ms = event_time_ms(epi, max(20, args.steps), stream)
     epi_gbs = 4.0 * T * H * eb / (epi_ms * 1e-3) / 1e9
 
-    extra = {"ffn1_fwd_gemm_bias_act": {"bound": "mfma", "achieved": ffn1_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+    # context for "achievable" HBM bandwidth: a plain device-to-device copy of 256 MiB (read + write counted)
+    csrc = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    cdst = torch.empty_like(csrc)
+    for _ in range(3):
+        cdst.copy_(csrc)
+    copy_ms = event_time_ms(lambda: cdst.copy_(csrc), 20, stream)
+    copy_gbs = 2.0 * (256 << 20) / (copy_ms * 1e-3) / 1e9
+    del csrc, cdst
+
+    extra = {"copy_kernel_256MiB": {"achieved": copy_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": copy_gbs / HBM_PEAK_GBS},
+             "ffn1_fwd_gemm_bias_act": {"bound": "mfma", "achieved": ffn1_tf, "peak": MFMA_BF16_PEAK_TFLOPS,
                                         "unit": "TFLOP/s", "frac": ffn1_tf / MFMA_BF16_PEAK_TFLOPS,
                                         "avg_launch_us": ffn1_ms * 1e3},
              "layer_tflops": total_flops / (ms * 1e-3) / 1e12,
