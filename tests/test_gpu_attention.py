@@ -59,3 +59,34 @@ def test_attention_fwd_bwd(dtype, case):
                      torch.from_numpy(LSE_ref.astype(np.float32)).to(DEV), delta, dqkv)
     for i, name in enumerate(("dq", "dk", "dv")):
         assert err(dqkv[:, i * H:(i + 1) * H], dqkv_ref[:, i * H:(i + 1) * H]) <= tol, name
+
+
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP32, W.FP16])
+@pytest.mark.parametrize("causal", [0, 1])
+def test_sample_without_visible_keys_yields_zeros_not_nans(dtype, causal):
+    """Outside the documented precondition (len >= 1) the kernels still behave: a sample whose length is 0 gets
+    zero output, -inf logsumexp and zero gradients, and leaves its neighbours untouched."""
+    Bt, S, h, d = 3, 136, 2, 64
+    H = h * d
+    cfg = W.LayerConfig("t", Bt, S, H, h, 64, causal=causal, dtype=dtype)
+    rng = np.random.default_rng(11)
+    qkv = store(rng.standard_normal((Bt * S, 3 * H)), dtype)
+    dout = store(rng.standard_normal((Bt * S, H)), dtype)
+    sl = np.array([S, 0, 70], dtype=np.int32)
+    desc = B.make_desc(cfg)
+    qkv_d, sl_d = to_dev(qkv, dtype), torch.from_numpy(sl).to(DEV)
+    out = torch.full((Bt * S, H), float("nan"), dtype=qkv_d.dtype, device=DEV)
+    lse = torch.full((Bt, h, S), float("nan"), dtype=torch.float32, device=DEV)
+    B.slapo_attn_fwd(desc, qkv_d, sl_d, out, lse)
+    assert torch.isfinite(out).all() and (out[S:2 * S] == 0).all() and torch.isneginf(lse[1]).all()
+    # the other two samples equal a run in which the empty one is given a length
+    ok = np.array([S, 5, 70], dtype=np.int32)
+    A_ref, P, LSE_ref = L.attention_fwd(cfg, qkv.astype(np.float64), ok)
+    keep = np.r_[0:S, 2 * S:3 * S]
+    assert err(out[keep], A_ref[keep]) <= TOL[dtype]
+    delta = torch.empty(Bt, h, S, dtype=torch.float32, device=DEV)
+    dqkv = torch.full((Bt * S, 3 * H), float("nan"), dtype=qkv_d.dtype, device=DEV)
+    B.slapo_attn_bwd(desc, qkv_d, sl_d, out, to_dev(dout, dtype), lse, delta, dqkv)
+    assert torch.isfinite(dqkv).all() and (dqkv[S:2 * S] == 0).all()
+    dqkv_ref = L.attention_bwd(cfg, qkv.astype(np.float64), P, dout.astype(np.float64))
+    assert err(dqkv[keep], dqkv_ref[keep]) <= TOL[dtype]
