@@ -258,7 +258,8 @@ def main():
         torch.cuda.synchronize()
     # for reference: the largest forward GEMM with its fused bias+activation epilogue (FFN1)
     y1 = layer.saved_tensor("n2" if cfg.pre_ln else "y1")
-    u = layer.saved_tensor("dgate" if llama else "dact")
+    # (a ReLU layer keeps no derivative: its gate is read off the activation output)
+    u = layer.saved_tensor("dgate") if llama else layer.saved_tensor("dact") if act == W.GELU else None
     g = torch.empty(T * F, device="cuda", dtype=tdt)
 
     def ffn1():

@@ -118,7 +118,8 @@ int slapo_layer_workspace(const slapo_layer_desc *desc, size_t *saved_bytes, siz
 /* Named regions inside `saved`, for tests and tools. Writes byte offset and byte length; returns
  * SLAPO_ERR_UNSUPPORTED if the region does not exist for this wiring. Names: "qkv" [T,3H], "attn"
  * [T,H], "lse" [B,heads,S] fp32, "z1" [T,H], "n1" (pre-LN) [T,H], "y1" (post-LN) / "n2" (pre-LN)
- * [T,H], "dact" [T,F] (act'(u) of the FFN pre-activation u), "g" [T,F], "z2" (post-LN) [T,H], "mu1","rstd1","mu2","rstd2" [T] fp32.
+ * [T,H], "dact" [T,F] (act'(u) of the FFN pre-activation u; GeLU layers only, a ReLU layer reads its gate
+ * off "g"), "g" [T,F], "z2" (post-LN) [T,H], "mu1","rstd1","mu2","rstd2" [T] fp32.
  * SLAPO_ARCH_LLAMA: "qkv" holds the rotated queries and keys, "dgate" [T,2F] replaces "dact" (column 2c:
  * up_c * silu'(gate_c), column 2c+1: silu(gate_c)), "mu1"/"mu2" are unused. */
 int slapo_layer_saved_region(const slapo_layer_desc *desc, const char *name, size_t *offset, size_t *bytes);
@@ -171,8 +172,10 @@ const char *slapo_status_string(int status);
  *   layout 2 (TN): A [K,M], B [K,N]   -- weight gradients dY^T X
  *   epilogue 0: C = acc                       1: C = acc + bias[n]
  *            2: u = acc + bias[n]; C = act(u), aux_out = act'(u)   (F.gelu(bias + x), appendix schedule;
- *               the derivative is all that backward needs of u, and its terms are at hand here)
- *            3: C = acc * aux_in[m,n] (aux_in = the aux_out of epilogue 2)   4: C = acc + aux_in[m,n]  (aux_in may alias C)
+ *               the derivative is all that backward needs of u, and its terms are at hand here; with
+ *               act = SLAPO_RELU aux_out may be NULL: the derivative [u > 0] equals [C > 0])
+ *            3: GeLU: C = acc * aux_in[m,n] (aux_in = the aux_out of epilogue 2); ReLU: C = acc * [aux_in[m,n] > 0]
+ *               (aux_in = the C or the aux_out of epilogue 2)   4: C = acc + aux_in[m,n]  (aux_in may alias C)
  *            5: columns are (gate, up) pairs (N % 16 == 0): C [M,N/2] = silu(gate) * up,
  *               aux_out [M,N] = (up * silu'(gate), silu(gate)) per pair            (SwiGLU forward)
  *            6: C [M,2N] = (acc * aux_in[m,2n], acc * aux_in[m,2n+1]), aux_in [M,2N] = the aux_out of

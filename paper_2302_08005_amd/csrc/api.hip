@@ -47,6 +47,7 @@ int check_desc(const slapo_layer_desc* d) {
 }
 
 inline bool is_llama(const slapo_layer_desc* d) { return d->arch == SLAPO_ARCH_LLAMA; }
+inline bool keeps_dact(const slapo_layer_desc* d) { return is_llama(d) || d->act != SLAPO_RELU; }
 // The pointer tables list weight, bias (or gain, offset) alternately; the LLaMA-style layer has the six
 // weights and gains only, i.e. the even entries.
 inline bool param_needed(const slapo_layer_desc* d, int index) { return !is_llama(d) || index % 2 == 0; }
@@ -133,7 +134,9 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
   L.z1 = take(T * H * eb);
   L.n1 = d->pre_ln ? take(T * H * eb) : (size_t)-1;
   L.y1 = take(T * H * eb);  // post-LN: LN1 output; pre-LN: LN2 output ("n2")
-  L.u = take(T * F * eb * (is_llama(d) ? 2 : 1));   // act'(u), or the (gate, up) factor pairs [T,2F]
+  // act'(u) of a GeLU layer, or the (gate, up) factor pairs [T,2F]; a ReLU layer keeps nothing here: its
+  // derivative is [g > 0], read off the activation output it keeps anyway
+  L.u = keeps_dact(d) ? take(T * F * eb * (is_llama(d) ? 2 : 1)) : (size_t)-1;
   L.g = take(T * F * eb);
   L.z2 = d->pre_ln ? (size_t)-1 : take(T * H * eb);
   L.mu1 = take(T * 4);
@@ -223,7 +226,7 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
   else if (!strcmp(name, "n1")) { off = L.n1; len = T * H * eb; }
   else if (!strcmp(name, "y1") && !desc->pre_ln) { off = L.y1; len = T * H * eb; }
   else if (!strcmp(name, "n2") && desc->pre_ln) { off = L.y1; len = T * H * eb; }
-  else if (!strcmp(name, "dact") && !is_llama(desc)) { off = L.u; len = T * F * eb; }
+  else if (!strcmp(name, "dact") && !is_llama(desc) && keeps_dact(desc)) { off = L.u; len = T * F * eb; }
   else if (!strcmp(name, "dgate") && is_llama(desc)) { off = L.u; len = 2 * T * F * eb; }
   else if (!strcmp(name, "g")) { off = L.g; len = T * F * eb; }
   else if (!strcmp(name, "z2")) { off = L.z2; len = T * H * eb; }
@@ -247,7 +250,8 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   const ScratchLayout W = scratch_layout(d);
   char* sv = (char*)saved;
   char* sc = (char*)scratch;
-  void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *u = sv + L.u, *g = sv + L.g;
+  void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *g = sv + L.g;
+  void* u = keeps_dact(d) ? sv + L.u : nullptr;
   float *lse = (float*)(sv + L.lse), *mu1 = (float*)(sv + L.mu1), *rstd1 = (float*)(sv + L.rstd1);
   float *mu2 = (float*)(sv + L.mu2), *rstd2 = (float*)(sv + L.rstd2);
   void* r = sc + W.t0;
@@ -330,7 +334,8 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   }
   const char* sv = (const char*)saved;
   char* sc = (char*)scratch;
-  const void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *u = sv + L.u, *g = sv + L.g;
+  const void *qkv = sv + L.qkv, *attn = sv + L.attn, *z1 = sv + L.z1, *y1 = sv + L.y1, *g = sv + L.g;
+  const void* u = keeps_dact(d) ? sv + L.u : g;   // ReLU: the gate [g > 0] comes from the activation output
   const float *lse = (const float*)(sv + L.lse), *mu1 = (const float*)(sv + L.mu1), *rstd1 = (const float*)(sv + L.rstd1);
   const float *mu2 = (const float*)(sv + L.mu2), *rstd2 = (const float*)(sv + L.rstd2);
   void *t0 = sc + W.t0, *t1 = sc + W.t1, *t2 = sc + W.t2, *t3 = sc + W.t3, *du = sc + W.du, *dqkv = sc + W.dqkv;
@@ -496,7 +501,7 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
   if (M * N >= ((int64_t)1 << 31) || M * K >= ((int64_t)1 << 31) || N * K >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if (!A || !B || !C) return SLAPO_ERR_NULL;
   if ((epilogue == EPI_BIAS || epilogue == EPI_BIAS_ACT) && !bias) return SLAPO_ERR_NULL;
-  if ((epilogue == EPI_BIAS_ACT || epilogue == EPI_GATE) && !aux_out) return SLAPO_ERR_NULL;
+  if (((epilogue == EPI_BIAS_ACT && act != SLAPO_RELU) || epilogue == EPI_GATE) && !aux_out) return SLAPO_ERR_NULL;
   if ((epilogue == EPI_DACT || epilogue == EPI_ADD || epilogue == EPI_DGATE) && !aux_in) return SLAPO_ERR_NULL;
   if (epilogue == EPI_DGATE && 2 * M * N >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
   if (N % 8 || (epilogue == EPI_GATE && N % 16)) return SLAPO_ERR_ALIGN;

@@ -60,10 +60,11 @@ __device__ __forceinline__ void epilogue_store(int epi, int act, float acc, int6
     v += to_f32(bias[n]);
   } else if (epi == EPI_BIAS_ACT) {
     v += to_f32(bias[n]);
-    from_f32(aux_out[idx], act_grad(v, act));   // all that backward needs of the pre-activation
+    if (aux_out) from_f32(aux_out[idx], act_grad(v, act));   // all that backward needs of the pre-activation
     v = act_fwd(v, act);
   } else if (epi == EPI_DACT) {
-    v *= to_f32(aux_in[idx]);
+    const float u = to_f32(aux_in[idx]);
+    v = act == ACT_RELU ? (u > 0.f ? v : 0.f) : v * u;
   } else if (epi == EPI_ADD) {
     v += to_f32(aux_in[idx]);
   }
@@ -577,12 +578,17 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
               v[e] *= g.phi;
             }
           }
-          store8h<F16>(aux_out + idx, dv);
+          if (aux_out) store8h<F16>(aux_out + idx, dv);   // (a ReLU layer keeps nothing: its gate is read off the output)
         } else if (EPI == EPI_DACT) {
           float u[8];
           aux_get(au[i][pass], u);
+          if (act == ACT_RELU) {   // aux_in is the activation output (or the stored 0/1 derivative): gate = [aux_in > 0]
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] *= u[e];
+            for (int e = 0; e < 8; ++e) v[e] = u[e] > 0.f ? v[e] : 0.f;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= u[e];
+          }
         } else if (EPI == EPI_ADD) {
           float u[8];
           aux_get(au[i][pass], u);

@@ -72,6 +72,11 @@ def test_saved_regions_are_disjoint_and_inside_the_buffer():
         assert spans[-1][0] + spans[-1][1] <= saved
         with pytest.raises(B.SlapoError):
             B.slapo_layer_saved_region(d, "y1" if pre_ln else "n1")
+        # a ReLU layer keeps no derivative of its activation: [relu(u) > 0] is read off "g"
+        r = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024, pre_ln=pre_ln, act=B.RELU)
+        assert B.slapo_layer_workspace(r)[0] == saved - 2 * 128 * 1024 * 2
+        with pytest.raises(B.SlapoError):
+            B.slapo_layer_saved_region(r, "dact")
 
 
 def test_stack_workspace_and_argument_checks():

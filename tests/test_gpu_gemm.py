@@ -65,8 +65,13 @@ def test_gemm_epilogues(dtype, act):
         clear = np.abs(acc + bias) > 1e-2
         assert np.array_equal(to_np(U)[clear], _dact(acc + bias, act)[clear])
     assert err(Cout, _act(acc + bias, act)) <= tol
-    B.slapo_gemm(dtype, B.NT, B.EPI_DACT, act, M, N, K, A, Wt, Cout, aux_in=auxd)                # C = acc * aux_in
-    assert err(Cout, acc * aux.astype(np.float64)) <= tol
+    if act == W.RELU:   # the derivative store is optional: the gate can be read off the output
+        C0 = torch.empty_like(Cout)
+        B.slapo_gemm(dtype, B.NT, B.EPI_BIAS_ACT, act, M, N, K, A, Wt, C0, bias=bd)
+        assert torch.equal(C0, Cout)
+    B.slapo_gemm(dtype, B.NT, B.EPI_DACT, act, M, N, K, A, Wt, Cout, aux_in=auxd)
+    # GeLU: C = acc * aux_in; ReLU: C = acc * [aux_in > 0], the same for aux_in = relu(u) and aux_in = relu'(u)
+    assert err(Cout, acc * (aux > 0 if act == W.RELU else aux.astype(np.float64))) <= tol
     B.slapo_gemm(dtype, B.NT, B.EPI_ADD, act, M, N, K, A, Wt, Cout, aux_in=auxd)
     assert err(Cout, acc + aux) <= tol
     C2 = auxd.clone()                          # in-place accumulate (aux_in aliases C)

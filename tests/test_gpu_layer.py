@@ -39,13 +39,16 @@ SMALL = [
 def teacher_force(layer, cfg, ref):
     """Overwrites the saved activations with the oracle's forward values (rounded to the storage type).
 
-    Used for the backward comparison of bf16 ReLU layers: the ReLU gate [u > 0] is a 0/1 decision taken from
-    the stored pre-activation, so both sides must take it from the same stored values; an end-to-end
-    run would flip the gate wherever the two forward passes differ by a rounding error around u = 0.
+    Used for the backward comparison of bf16 ReLU layers: the ReLU gate [u > 0] is a 0/1 decision that the
+    layer reads off its stored activation output g = relu(u), so both sides must take it from the same
+    stored values; an end-to-end run would flip the gate wherever the two forward passes differ by a
+    rounding error around u = 0.
     """
-    ref = dict(ref, DACT=L._act_grad(ref["U"], cfg.act))   # the layer keeps act'(U), not U
-    names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "dact": "DACT", "g": "G", "lse": "LSE", "mu1": "mu1", "rstd1": "rstd1",
+    ref = dict(ref, DACT=L._act_grad(ref["U"], cfg.act))   # a GeLU layer keeps act'(U), not U; a ReLU layer neither
+    names = {"qkv": "QKV", "attn": "A", "z1": "Z1", "g": "G", "lse": "LSE", "mu1": "mu1", "rstd1": "rstd1",
              "mu2": "mu2", "rstd2": "rstd2"}
+    if cfg.act == W.GELU:
+        names["dact"] = "DACT"
     names.update({"n1": "N1", "n2": "N2"} if cfg.pre_ln else {"y1": "Y1", "z2": "Z2"})
     for k, rk in names.items():
         dst = layer.saved_tensor(k)
