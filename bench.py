@@ -151,6 +151,8 @@ def main():
     ap.add_argument("--attn-dropout", type=float, default=0.0,
                     help="also drop attention probabilities with this probability (0 = the benchmark configuration)")
     ap.add_argument("--breakdown", action="store_true", help="also time each GEMM / kernel class (stderr)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="run the configuration as a stack of this many layers (default: the configuration's own count)")
     ap.add_argument("--tp", type=int, default=1,
                     help="time ONE rank's share of the layer sharded N ways along heads and FFN columns "
                          "(heads/N, attention width hidden/N, ffn/N; no collectives are run)")
@@ -173,6 +175,8 @@ def main():
         cfg = cfg.replace(attn_dropout_p=args.attn_dropout)
     if args.fp16:
         cfg = cfg.replace(dtype=W.FP16)
+    if args.layers > 0 and args.layers != cfg.n_layers:
+        cfg = cfg.replace(name=f"{cfg.name}-x{args.layers}", n_layers=args.layers)
     if args.tp > 1:
         if cfg.heads % args.tp or cfg.ffn % (8 * args.tp):
             sys.exit(f"bench.py: --tp {args.tp} does not divide {cfg.heads} heads / ffn {cfg.ffn}")

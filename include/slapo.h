@@ -152,8 +152,12 @@ int slapo_layer_bwd(const slapo_layer_desc *desc, const slapo_layer_params *para
  *            (may be NULL for one layer)
  *   saved:   device, n_layers x the `saved` buffer of one layer (size 0 / ignored with desc->checkpoint: then
  *            acts and x are all that survives the forward pass)
- *   scratch: device, one layer's scratch plus two [B,S,H] gradient buffers; free between calls
- * Sizes come from slapo_stack_workspace. Errors as for the layer calls; n_layers <= 0 is SLAPO_ERR_SHAPE. */
+ *   scratch: device, one layer's scratch plus two (pre-LN: four) [B,S,H] gradient buffers; free between calls
+ * Pre-LN stacks fuse across the layer boundary: the last forward kernel of a layer also writes the first
+ * LayerNorm of the layer above, the last backward kernel of a layer also writes the first gradient of the
+ * layer below. Results are bit for bit those of the layers called one at a time.
+ * Sizes come from slapo_stack_workspace. Errors as for the layer calls (every layer's tables are checked
+ * before the first launch); n_layers <= 0 is SLAPO_ERR_SHAPE. */
 int slapo_stack_workspace(const slapo_layer_desc *desc, int32_t n_layers, size_t *acts_bytes, size_t *saved_bytes,
                           size_t *scratch_bytes);
 int slapo_stack_fwd(const slapo_layer_desc *desc, int32_t n_layers, const slapo_layer_params *params, const void *x,

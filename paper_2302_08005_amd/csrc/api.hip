@@ -240,10 +240,22 @@ int slapo_layer_saved_region(const slapo_layer_desc* desc, const char* name, siz
   return SLAPO_OK;
 }
 
+// In a stack of pre-LN layers the LayerNorm that opens layer l+1 reads what the last kernel of layer l has
+// just written, so that kernel produces it on the way: the pattern (sum out, its LayerNorm out) is the one
+// the layer already uses between its attention and feed-forward blocks, and one pass over [T,H] per layer
+// boundary goes away. The normalised values are computed from the stored (rounded) sum, exactly as the
+// separate kernel would, so a layer run on its own reproduces them bit for bit.
+struct ForwardLink {
+  bool ln1_done = false;                       // the layer below has filled n1, mu1, rstd1 of `saved`
+  const slapo_layer_params* above = nullptr;   // the layer above: its first LayerNorm rides on my last kernel
+  void* above_saved = nullptr;                 // ... and lands in the n1, mu1, rstd1 regions of its `saved`
+};
+
 // The forward launch sequence; `saved` receives the activations. Also the first half of a checkpointed
-// backward, which is why it is a function of its own.
+// backward (`for_backward`), which is why it is a function of its own.
 static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
-                        void* y, void* saved, void* scratch, hipStream_t st) {
+                        void* y, void* saved, void* scratch, hipStream_t st, bool for_backward = false,
+                        const ForwardLink* link = nullptr) {
   const int dt = d->dtype;   // SLAPO_* element types are the launch interface's DT_* values
   const int T = d->batch * d->seq, H = d->hidden, F = d->ffn, A = attn_width(d);
   const SavedLayout L = saved_layout(d);
@@ -263,7 +275,8 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   const void* attn_in = x;
   if (d->pre_ln) {
     void* n1 = sv + L.n1;
-    launch_bdrln_fwd(dt, T, H, nullptr, nullptr, x, p->ln1_g, p->ln1_b, nullptr, n1, mu1, rstd1, dp0, d->ln_eps, rms, st);
+    if (!(link && link->ln1_done))
+      launch_bdrln_fwd(dt, T, H, nullptr, nullptr, x, p->ln1_g, p->ln1_b, nullptr, n1, mu1, rstd1, dp0, d->ln_eps, rms, st);
     attn_in = n1;
   }
   if (llama) {
@@ -285,8 +298,15 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
     launch_gemm(dt, GEMM_NT, EPI_GATE, d->act, T, 2 * F, H, y1, p->w1, g, nullptr, nullptr, u, st, true);
   else
     launch_gemm(dt, GEMM_NT, EPI_BIAS_ACT, d->act, T, F, H, y1, p->w1, g, p->b1, nullptr, u, st, true);
+  // Backward of a pre-LN layer reads nothing downstream of the activation output (its last step has no
+  // LayerNorm whose input would have to be kept), so a recomputation stops here: one GEMM in six less.
+  if (for_backward && d->pre_ln) return;
   launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st, true);
-  if (d->pre_ln) {
+  if (d->pre_ln && link && link->above) {
+    char* up = (char*)link->above_saved;
+    launch_bdrln_fwd(dt, T, H, r, b2, z1, link->above->ln1_g, llama ? nullptr : link->above->ln1_b, y, up + L.n1,
+                     (float*)(up + L.mu1), (float*)(up + L.rstd1), dp1, d->ln_eps, rms, st);
+  } else if (d->pre_ln) {
     launch_bdrln_fwd(dt, T, H, r, b2, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, dp1, d->ln_eps, rms, st);
   } else {
     void* z2 = sv + L.z2;
@@ -294,22 +314,28 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   }
 }
 
-int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
-                    void* y, void* saved, void* scratch, void* stream) {
+static int check_forward_args(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const void* y,
+                              const void* saved, const void* scratch) {
   int rc = check_desc(d);
   if (rc) return rc;
   if (!p || !x || !y || !scratch || (!saved && !d->checkpoint)) return SLAPO_ERR_NULL;
   const void* const ps[12] = {p->wqkv, p->bqkv, p->wo, p->bo, p->ln1_g, p->ln1_b, p->w1, p->b1, p->w2, p->b2, p->ln2_g, p->ln2_b};
   if ((rc = check_tables(d, ps))) return rc;
   if (misaligned(x) || misaligned(y) || misaligned(scratch) || (!d->checkpoint && misaligned(saved))) return SLAPO_ERR_ALIGN;
+  return SLAPO_OK;
+}
+
+int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
+                    void* y, void* saved, void* scratch, void* stream) {
+  const int rc = check_forward_args(d, p, x, y, saved, scratch);
+  if (rc) return rc;
   if (d->checkpoint) saved = (char*)scratch + scratch_layout(d).acts;   // transient: nothing is kept for backward
   run_forward(d, p, x, seqlens, y, saved, scratch, (hipStream_t)stream);
   return finish();
 }
 
-int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
-                    const void* dy, const void* saved, void* dx, const slapo_layer_grads* gr, void* scratch,
-                    void* stream) {
+static int check_backward_args(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const void* dy,
+                               const void* saved, const void* dx, const slapo_layer_grads* gr, const void* scratch) {
   int rc = check_desc(d);
   if (rc) return rc;
   if (!p || !x || !dy || !dx || !gr || !scratch || (!saved && !d->checkpoint)) return SLAPO_ERR_NULL;
@@ -317,8 +343,23 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   const void* const gs[12] = {gr->wqkv, gr->bqkv, gr->wo, gr->bo, gr->ln1_g, gr->ln1_b, gr->w1, gr->b1, gr->w2, gr->b2, gr->ln2_g, gr->ln2_b};
   if ((rc = check_tables(d, ps)) || (rc = check_tables(d, gs))) return rc;
   if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(scratch) || (!d->checkpoint && misaligned(saved))) return SLAPO_ERR_ALIGN;
+  return SLAPO_OK;
+}
 
-  hipStream_t st = (hipStream_t)stream;
+// The backward counterpart of ForwardLink: the last kernel of a pre-LN layer's backward (LayerNorm backward
+// plus the residual gradient -> dx) is also where the layer below would start (dx -> its dropped-out branch
+// gradient dR2 and the row sums behind its b2 gradient), so in a stack the upper layer's kernel writes both
+// and the lower layer starts at its first GEMM.
+struct BackwardLink {
+  const void* dr2_in = nullptr;   // my dR2, already produced (with my b2 gradient) by the layer above
+  void* dr2_below = nullptr;      // where the dR2 of the layer below goes ...
+  DropoutParams dp_below;         // ... its mask stream (site 1 of that layer)
+  void* db2_below = nullptr;      // ... and its b2 gradient (NULL: the family has no biases)
+};
+
+static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
+                        const void* dy, const void* saved, void* dx, const slapo_layer_grads* gr, void* scratch,
+                        hipStream_t st, const BackwardLink* link = nullptr) {
   const int dt = d->dtype, acc = d->accumulate_grads ? 1 : 0;
   const int T = d->batch * d->seq, H = d->hidden, F = d->ffn, A = attn_width(d);
   const SavedLayout L = saved_layout(d);
@@ -329,7 +370,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     // site, element), so the recomputed activations are bit for bit those of the original forward. The layer
     // output lands in a gradient buffer that backward overwrites later.
     char* acts = (char*)scratch + W.acts;
-    run_forward(d, p, x, seqlens, (char*)scratch + W.t1, acts, scratch, st);
+    run_forward(d, p, x, seqlens, (char*)scratch + W.t1, acts, scratch, st, true);
     saved = acts;
   }
   const char* sv = (const char*)saved;
@@ -372,7 +413,10 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   void *g_ln1_b = llama ? nullptr : gr->ln1_b, *g_ln2_b = llama ? nullptr : gr->ln2_b;
 
   // ---- FFN block ----
-  if (d->pre_ln) {
+  const void* dr2 = t1;
+  if (d->pre_ln && link && link->dr2_in) {
+    dr2 = link->dr2_in;
+  } else if (d->pre_ln) {
     launch_bdrln_bwd(dt, T, H, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, t1, prow, dp1, rms, st);
     if (!llama) reduce_rows(nullptr, nullptr, g_b2);
   } else {
@@ -380,15 +424,15 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     reduce_rows(gr->ln2_g, g_ln2_b, g_b2);
   }
   fork(0);
-  dweight(H, F, t1, g, gr->w2);
+  dweight(H, F, dr2, g, gr->w2);
   if (llama) {
     // dG = dR2 W2, turned into the (gate, up) gradient pairs [T,2F] by the two saved factors in the epilogue
-    launch_gemm(dt, GEMM_NN, EPI_DGATE, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st, solo);
+    launch_gemm(dt, GEMM_NN, EPI_DGATE, d->act, T, F, H, dr2, p->w2, du, nullptr, u, nullptr, st, solo);
     fork(1);
     dweight(2 * F, H, du, y1, gr->w1);
     launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 2 * F, du, p->w1, t0, nullptr, nullptr, nullptr, st, solo);
   } else {
-    launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, t1, p->w2, du, nullptr, u, nullptr, st, solo);
+    launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, dr2, p->w2, du, nullptr, u, nullptr, st, solo);
     fork(1);
     colsum(du, F, gr->b1, ws);
     dweight(F, H, du, y1, gr->w1);
@@ -417,8 +461,14 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
   if (d->pre_ln) {
     dweight(3 * A, H, dqkv, sv + L.n1, gr->wqkv);
     launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * A, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st, solo);
-    launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, rms, st);
-    reduce_rows(gr->ln1_g, g_ln1_b, nullptr);
+    if (link && link->dr2_below) {
+      // (from the stored dx, so that the layer below sees what it would compute from dx itself, bit for bit)
+      launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, link->dr2_below, prow, link->dp_below, rms, st, 1);
+      reduce_rows(gr->ln1_g, g_ln1_b, link->db2_below);
+    } else {
+      launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, nullptr, prow, dp0, rms, st);
+      reduce_rows(gr->ln1_g, g_ln1_b, nullptr);
+    }
   } else {
     dweight(3 * A, H, dqkv, x, gr->wqkv);
     launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * A, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st, solo);
@@ -431,6 +481,14 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
     (void)hipStreamWaitEvent(st, side->join, 0);
   }
   return finish();
+}
+
+int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, const void* x, const int32_t* seqlens,
+                    const void* dy, const void* saved, void* dx, const slapo_layer_grads* gr, void* scratch,
+                    void* stream) {
+  const int rc = check_backward_args(d, p, x, dy, saved, dx, gr, scratch);
+  if (rc) return rc;
+  return run_backward(d, p, x, seqlens, dy, saved, dx, gr, scratch, (hipStream_t)stream);
 }
 
 // ---- a stack of layers of one shape ------------------------------------------------------------------
@@ -446,7 +504,9 @@ int slapo_stack_workspace(const slapo_layer_desc* desc, int32_t n_layers, size_t
   if (n_layers <= 0) return SLAPO_ERR_SHAPE;
   *acts_bytes = (size_t)(n_layers - 1) * stack_act_bytes(desc);
   *saved_bytes = desc->checkpoint ? 0 : (size_t)n_layers * saved_layout(desc).total;
-  *scratch_bytes = scratch_layout(desc).total + 2 * align256(stack_act_bytes(desc));
+  // behind the layer's own scratch: two alternating buffers for the gradient that flows down the stack and,
+  // for pre-LN layers, two for the branch gradient that each layer's last kernel prepares for the layer below
+  *scratch_bytes = scratch_layout(desc).total + (desc->pre_ln ? 4 : 2) * align256(stack_act_bytes(desc));
   return SLAPO_OK;
 }
 
@@ -458,14 +518,27 @@ int slapo_stack_fwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
   if (!params || !x || !y || !scratch || (n_layers > 1 && !acts) || (!saved && !desc->checkpoint)) return SLAPO_ERR_NULL;
   const size_t ab = stack_act_bytes(desc), sb = desc->checkpoint ? 0 : saved_layout(desc).total;
   slapo_layer_desc d = *desc;
+  // every layer is checked before the first launch, so that a bad table leaves nothing half done
+  for (int l = 0; l < n_layers; ++l) {
+    const void* in = l == 0 ? x : (const char*)acts + (size_t)(l - 1) * ab;
+    void* out = l == n_layers - 1 ? y : (char*)acts + (size_t)l * ab;
+    if ((rc = check_forward_args(&d, params + l, in, out, saved, scratch))) return rc;
+  }
+  // with checkpointing every layer works in the same transient region, whose contents die with the layer
+  char* transient = (char*)scratch + scratch_layout(desc).acts;
+  auto saved_of = [&](int l) -> void* { return desc->checkpoint ? transient : (char*)saved + (size_t)l * sb; };
   for (int l = 0; l < n_layers; ++l) {
     d.layer_id = desc->layer_id + l;
     const void* in = l == 0 ? x : (const char*)acts + (size_t)(l - 1) * ab;
     void* out = l == n_layers - 1 ? y : (char*)acts + (size_t)l * ab;
-    rc = slapo_layer_fwd(&d, params + l, in, seqlens, out, saved ? (char*)saved + (size_t)l * sb : nullptr, scratch, stream);
-    if (rc) return rc;
+    ForwardLink link;
+    if (d.pre_ln) {   // the first LayerNorm of layer l+1 rides on the last kernel of layer l
+      link.ln1_done = l > 0;
+      if (l + 1 < n_layers) { link.above = params + l + 1; link.above_saved = saved_of(l + 1); }
+    }
+    run_forward(&d, params + l, in, seqlens, out, saved_of(l), scratch, (hipStream_t)stream, false, &link);
   }
-  return SLAPO_OK;
+  return finish();
 }
 
 int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_layer_params* params, const void* x,
@@ -478,14 +551,32 @@ int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
     return SLAPO_ERR_NULL;
   const size_t ab = stack_act_bytes(desc), sb = desc->checkpoint ? 0 : saved_layout(desc).total;
   char* pong = (char*)scratch + scratch_layout(desc).total;   // two gradient buffers behind the layer's own scratch
+  char* carry = pong + 2 * align256(ab);                      // (pre-LN) two branch-gradient buffers behind those
   slapo_layer_desc d = *desc;
+  for (int l = 0; l < n_layers; ++l) {   // every layer is checked before the first launch
+    const void* in = l == 0 ? x : (const char*)acts + (size_t)(l - 1) * ab;
+    if ((rc = check_backward_args(&d, params + l, in, dy, saved, dx, grads + l, scratch))) return rc;
+  }
   const void* gin = dy;
   for (int l = n_layers - 1; l >= 0; --l) {
     d.layer_id = desc->layer_id + l;
     const void* in = l == 0 ? x : (const char*)acts + (size_t)(l - 1) * ab;
     void* gout = l == 0 ? dx : pong + (size_t)(l & 1) * align256(ab);
-    rc = slapo_layer_bwd(&d, params + l, in, seqlens, gin, saved ? (const char*)saved + (size_t)l * sb : nullptr, gout,
-                         grads + l, scratch, stream);
+    BackwardLink link;
+    if (d.pre_ln) {
+      // Layer l reads buffer l&1 (on both streams) and writes the other one; that one was last read by the
+      // weight gradient of layer l+1, which the join at the end of that layer's backward has waited for.
+      if (l + 1 < n_layers) link.dr2_in = carry + (size_t)(l & 1) * align256(ab);
+      if (l > 0) {
+        slapo_layer_desc below = d;
+        below.layer_id = d.layer_id - 1;
+        link.dr2_below = carry + (size_t)((l - 1) & 1) * align256(ab);
+        link.dp_below = make_dropout(&below, 1);
+        link.db2_below = is_llama(desc) ? nullptr : grads[l - 1].b2;
+      }
+    }
+    rc = run_backward(&d, params + l, in, seqlens, gin, saved ? (const char*)saved + (size_t)l * sb : nullptr, gout,
+                      grads + l, scratch, (hipStream_t)stream, &link);
     if (rc) return rc;
     gin = gout;
   }

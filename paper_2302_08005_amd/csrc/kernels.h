@@ -41,7 +41,7 @@ void launch_bdrln_fwd(int dtype, int64_t rows, int H, const void* r, const void*
 int bdrln_bwd_blocks(int64_t rows);
 void launch_bdrln_bwd(int dtype, int64_t rows, int H, const void* dout, const void* z, const float* mu,
                       const float* rstd, const void* gamma, const void* dres_in, void* dz_out, void* dr_out,
-                      float* partials, const DropoutParams& dp, int rms, hipStream_t st);
+                      float* partials, const DropoutParams& dp, int rms, hipStream_t st, int dr_from_stored = 0);
 // Rotary embedding on the Q and K parts of a packed [rows, 3H] array, in place: inside every head of width d
 // the adjacent pair (2j, 2j+1) of row t is turned by the angle of table entry (t % seq, j) (negated when
 // `inverse`). table: [seq, d/2] (cos, sin) pairs in fp32, written by launch_rope_table (angle m * base^(-2j/d),

@@ -78,12 +78,26 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_fwd_kernel(
   }
 }
 
+// Replaces eight fp32 values by what they read back as after a store in the element type: a kernel that
+// goes on from them then computes exactly what a separate kernel reading the stored array would.
+template <typename T>
+__device__ __forceinline__ void round_as(float (&v)[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    T h;
+    from_f32(h, v[j]);
+    v[j] = to_f32(h);
+  }
+}
+
 // Backward of out = LN(z), z = res + keep*(r+bias)*scale.  See slapo_bdrln_bwd for the contract.
+// dr_from_stored: the branch gradient dr is derived from dz as stored (rounded to T) rather than from the
+// fp32 value, i.e. dz_out and dr_out are those of two kernels in a row (dz first, then dr from the stored dz).
 template <typename T, int NCH, bool LN, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
     int64_t rows, int H, const T* __restrict__ dout, const T* __restrict__ z, const float* __restrict__ mu,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres_in,
-    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp) {
+    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp, int dr_from_stored) {
   extern __shared__ float red[];  // [WAVES/2][3][H]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nchunk = H >> 3;
@@ -160,6 +174,7 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
         }
         if (dz_out) store8(dz_out + base + c * 8, dz);
         if (dr_out) {
+          if (dr_from_stored) round_as<T>(dz);
           const uint32_t keep = dropout_keep8(dp, (uint64_t)(base >> 3) + (uint64_t)c);
           float dr[8];
 #pragma unroll
@@ -228,7 +243,7 @@ template <typename T, bool LN, int R>
 __global__ __launch_bounds__(512) void bdrln_bwd_wide_kernel(
     int64_t rows, int H, const T* __restrict__ dout, const T* __restrict__ z, const float* __restrict__ mu,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres_in,
-    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp) {
+    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp, int dr_from_stored) {
   __shared__ float xs[2][R][8][2];   // [parity][row][wave][s1, s2]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int c = threadIdx.x;
@@ -307,6 +322,7 @@ __global__ __launch_bounds__(512) void bdrln_bwd_wide_kernel(
         }
         if (dz_out) store8(dz_out + base + c * 8, dz);
         if (dr_out) {
+          if (dr_from_stored) round_as<T>(dz);
           const uint32_t keep = dropout_keep8(dp, (uint64_t)(base >> 3) + (uint64_t)c);
           float dr[8];
 #pragma unroll
@@ -450,12 +466,13 @@ int bdrln_bwd_blocks(int64_t rows) {
 template <typename T, bool LN>
 static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, const float* mu, const float* rstd,
                        const void* gamma, const void* dres_in, void* dz_out, void* dr_out, float* partials,
-                       const DropoutParams& dp, hipStream_t st) {
+                       const DropoutParams& dp, int dr_from_stored, hipStream_t st) {
   const int blocks = bdrln_bwd_blocks(rows);
   if (H / 8 > 128) {   // wide rows: columns split over the wavefronts of a block (H <= 4096: at most 8 of them)
     const int waves = (H / 8 + 63) / 64;
     hipLaunchKernelGGL((bdrln_bwd_wide_kernel<T, LN, 4>), dim3(blocks), dim3(waves * 64), 0, st, rows, H, (const T*)dout,
-                       (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp);
+                       (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,
+                       dr_from_stored);
     return;
   }
 #define SLAPO_BWD(N, W)                                                                                      \
@@ -464,7 +481,8 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
     const size_t lds = (size_t)(W / 2) * 3 * H * 4;                                                          \
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(W * 64), lds, st, rows, H, (const T*)dout, (const T*)z, mu,  \
-                       rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp);      \
+                       rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,       \
+                       dr_from_stored);                                                                      \
   } while (0)
   switch (nch_for(H)) {
     case 1: SLAPO_BWD(1, 8); break;
@@ -475,12 +493,12 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
 
 void launch_bdrln_bwd(int dtype, int64_t rows, int H, const void* dout, const void* z, const float* mu,
                       const float* rstd, const void* gamma, const void* dres_in, void* dz_out, void* dr_out,
-                      float* partials, const DropoutParams& dp, int rms, hipStream_t st) {
+                      float* partials, const DropoutParams& dp, int rms, hipStream_t st, int dr_from_stored) {
   if (rms) mu = nullptr;   // the kernel reads a missing mean as RMSNorm (mean 0, no mean-of-gradient term)
   const bool ln = gamma != nullptr;
 #define SLAPO_PICK(T)                                                                                          \
-  if (ln) launch_bwd<T, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st);     \
-  else launch_bwd<T, false>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, st)
+  if (ln) launch_bwd<T, true>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, dr_from_stored, st); \
+  else launch_bwd<T, false>(rows, H, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials, dp, dr_from_stored, st)
   if (dtype == DT_FP32) { SLAPO_PICK(float); } else if (dtype == DT_FP16) { SLAPO_PICK(f16_t); } else { SLAPO_PICK(bf16_t); }
 #undef SLAPO_PICK
 }

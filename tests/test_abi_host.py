@@ -86,6 +86,10 @@ def test_stack_workspace_and_argument_checks():
     act = 2 * 128 * 256 * 2
     assert acts == 23 * act and ssaved == 24 * saved and scratch + 2 * act <= sscratch <= scratch + 2 * act + 512
     assert B.slapo_stack_workspace(d, 1)[0] == 0
+    # pre-LN stacks hand the branch gradient from each layer to the one below through two more buffers
+    pre = B.make_desc(batch=2, seq=128, hidden=256, heads=4, ffn=1024, pre_ln=1)
+    pscratch = B.slapo_layer_workspace(pre)[1]
+    assert pscratch + 4 * act <= B.slapo_stack_workspace(pre, 24)[2] <= pscratch + 4 * act + 1024
     with pytest.raises(B.SlapoError) as e:
         B.slapo_stack_workspace(d, 0)
     assert e.value.status == -2

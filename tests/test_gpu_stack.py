@@ -70,6 +70,15 @@ def test_stack_matches_oracle_chain_and_single_layer_calls(cfg):
     for lay in layers:
         hs.append(lay.forward(hs[-1], sld))
     assert torch.equal(hs[-1], y)
+    # in a pre-LN stack each layer's opening LayerNorm is produced by the last kernel of the layer below:
+    # what lands in the layer's saved regions must be what the layer computes when called on its own
+    if cfg.pre_ln:
+        per_layer = st.saved.numel() // N_LAYERS
+        for l in range(1, N_LAYERS):
+            for name in ("n1", "rstd1") + (() if cfg.arch == W.LLAMA else ("mu1",)):
+                off, nb = B.slapo_layer_saved_region(st.desc, name)
+                mine = st.saved[l * per_layer + off:l * per_layer + off + nb]
+                assert torch.equal(mine, layers[l].saved[off:off + nb]), (l, name)
     g = dyd
     for l in reversed(range(N_LAYERS)):
         g = layers[l].backward(hs[l], sld, g)
