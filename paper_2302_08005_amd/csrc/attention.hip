@@ -68,6 +68,22 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& v, int h) {
   w.z = pack2<F16>(v[8 * h + 4], v[8 * h + 5]); w.w = pack2<F16>(v[8 * h + 6], v[8 * h + 7]);
   return __builtin_bit_cast(bf16x8_t, w);
 }
+// acc += a b with the accumulator held in the accumulation registers (AGPRs). The dK/dV kernel of 128-wide heads
+// needs 128 registers for its two output accumulators alone; as ordinary registers they leave so few for
+// operands that fragments and the K/V operands are shuttled in and out of spill registers inside the loop. The
+// compiler's MFMA form is one choice per translation unit (here: results in ordinary registers, because
+// scores feed vector arithmetic), so these accumulations are written out. The instruction is opaque to the
+// compiler's hazard pass, hence the two wait states in front (vector-ALU write of an operand -> MFMA read);
+// waits for LDS reads are still inserted by the compiler (it tracks the operand registers), accumulations
+// into one register are at least four MFMAs apart in program order, and the caller waits before reading
+// the result with ordinary instructions (agpr_results_ready).
+template <bool F16>
+__device__ __forceinline__ void mfma16_agpr(f32x16_t& acc, bf16x8_t a, bf16x8_t b) {
+  if constexpr (F16) asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  else asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// more wait states than any MFMA needs before its result may be read by a non-MFMA instruction
+__device__ __forceinline__ void agpr_results_ready() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 // row index inside a 32x32 accumulator tile of register r
 __device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + 4 * (lane >> 5) + (r & 3); }
 
@@ -84,6 +100,7 @@ template <int D>
 struct TileDirect {
   static constexpr int SPR = D / 8 + 1;            // 16-byte slots per padded row = wave-level loads per tile
   static constexpr int MINE = (SPR + 3) / 4;       // loads per tile of one wavefront (at most)
+  static constexpr int LEAST = SPR / 4;            // ... and at least
   unsigned voff[MINE];
   int wave;                                        // wave-uniform
   __device__ __forceinline__ void init(int lane, int wave_uniform, unsigned row_stride_bytes) {
@@ -104,6 +121,33 @@ struct TileDirect {
   }
 };
 
+// The tile loop of the forward kernel: a ring of NSTG LDS stages, tiles t+1 .. t+NSTG-1 on their way while
+// tile t is computed, one barrier per tile. LPT = loads every wavefront issues per tile step at the least:
+// waiting until at most (NSTG-2)*LPT loads are outstanding leaves only younger tiles in flight (loads
+// complete in issue order). On the last steps nothing is issued any more and the wait is for everything.
+template <int NSTG, int LPT, typename Issue, typename Compute>
+__device__ __forceinline__ void tile_ring(int n_tiles, Issue&& issue_tile, Compute&& compute) {
+  static_assert(NSTG >= 2, "ring");
+  if (n_tiles <= 0) return;
+#pragma unroll
+  for (int t = 0; t < NSTG - 1; ++t)
+    if (t < n_tiles) issue_tile(t, t);
+  if (n_tiles >= NSTG - 1) wait_loads_and_lds<(NSTG - 2) * LPT>();
+  else wait_loads_and_lds<0>();
+  block_barrier();
+  int stage = 0, fill = NSTG - 1;   // stage of tile `it`, stage that tile it + NSTG - 1 goes to
+  for (int it = 0; it < n_tiles; ++it) {
+    const bool more = it + NSTG - 1 < n_tiles;
+    if (more) issue_tile(fill, it + NSTG - 1);   // that stage was last read before the barrier that ended step it - 1
+    compute(stage, it);
+    if (more) wait_loads_and_lds<(NSTG - 2) * LPT>();
+    else wait_loads_and_lds<0>();
+    block_barrier();
+    stage = stage + 1 == NSTG ? 0 : stage + 1;
+    fill = fill + 1 == NSTG ? 0 : fill + 1;
+  }
+}
+
 __device__ __forceinline__ int visible_keys(const AttnShape& sh, const int32_t* seqlens, int b) {
   int n = sh.seq;
   if (seqlens) { const int v = seqlens[b]; n = v < n ? v : n; n = n < 0 ? 0 : n; }
@@ -113,13 +157,17 @@ __device__ __forceinline__ int visible_keys(const AttnShape& sh, const int32_t* 
 // Workgroups are handed to the 8 XCDs round-robin in launch order. The 128-row blocks of one (batch, head)
 // all read that head's K and V (or Q and dO), so they are renumbered to sit on the same XCD, next to each
 // other in time, and share the tiles through its L2 instead of each fetching them from memory.
+// With a causal mask the blocks of a head differ in work by a factor of the block count (query block x sees
+// x + 1 key blocks, key block x is seen by nx - x query blocks). `descending` walks a head's blocks from its
+// last to its first, for the kernels whose last block is the longest, so that in every kernel the long
+// blocks of a head start first and the grid ends on short ones instead of waiting for a long straggler.
 struct BlockId { int x, a, b; };
-__device__ __forceinline__ BlockId xcd_local_block() {
+__device__ __forceinline__ BlockId xcd_local_block(bool descending = false) {
   const int nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
   int w = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
   if (total % 8 == 0) w = (w & 7) * (total >> 3) + (w >> 3);
   BlockId id;
-  id.x = w % nx;
+  id.x = descending ? nx - 1 - w % nx : w % nx;
   id.a = (w / nx) % ny;
   id.b = w / (nx * ny);
   return id;
@@ -188,6 +236,11 @@ __device__ __forceinline__ uint32_t keep16_key_lane(const DropoutParams& dp, uin
 }
 
 // =================================== forward =====================================================
+// LDS stages of the forward kernel's K/V ring. Two: with three or four the forward pass is 10-40 % slower on
+// every shape with more than two workgroups per CU (the LDS footprint costs resident workgroups, and those,
+// not the depth of the prefetch, are what hides the latencies here) and unchanged on the others.
+template <int D> constexpr int FWD_STAGES = 2;
+
 template <int D, bool DROP, bool F16>
 __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                             const int32_t* __restrict__ seqlens,
@@ -196,7 +249,7 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
   constexpr int TE = Tile<D>::ELEMS;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int S = sh.seq, H = sh.hidden;
-  const BlockId blk = xcd_local_block();
+  const BlockId blk = xcd_local_block(sh.causal != 0);
   const int b = blk.b, a = blk.a, q_base = blk.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
   const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
@@ -303,15 +356,7 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(AttnShape sh, const 
           o[t] = mfma16<F16>(frag_tr<D>(vt, ft_base, i * 32 + 16 * h, t), pf, o[t]);
       }
   };
-  if (n_tiles > 0) {
-    issue_tile(0, 0);
-    __syncthreads();   // (waits for this wavefront's loads, then for everybody's)
-    for (int it = 0; it < n_tiles; ++it) {
-      if (it + 1 < n_tiles) issue_tile((it + 1) & 1, it + 1);   // that stage was last read before the barrier above
-      compute(it & 1, it);
-      __syncthreads();
-    }
-  }
+  tile_ring<FWD_STAGES<D>, 2 * TileDirect<D>::LEAST>(n_tiles, issue_tile, compute);
 
   const float l_tot = l + __shfl_xor(l, 32, 64);
   const float inv = l_tot > 0.f ? (DROP ? sh.drop.scale : 1.f) / l_tot : 0.f;
@@ -375,6 +420,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
   constexpr int NS = D / 16, NT = D / 32;
   constexpr int TE = Tile<D>::ELEMS;
   constexpr int STAGE = 2 * TE + 256;   // bf16 units: Q tile, dO tile, 64 lse + 64 delta floats
+  constexpr int FB = 4;                 // k-steps of fragment prefetch (register budget: 8 FB registers)
+  constexpr bool ACC_A = (D == 128);    // dK/dV accumulators in AGPRs (see mfma16_agpr)
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int S = sh.seq, H = sh.hidden;
   const BlockId blk = xcd_local_block();
@@ -445,11 +492,33 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
       f32x16_t sc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
+      // Fragments are requested FB k-steps ahead of the MFMAs that use them and the order is pinned: left to
+      // itself the scheduler reuses one register set for all fragments, and every MFMA then waits out the
+      // full LDS latency of its own read.
 #pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        sc = mfma16<F16>(frag_rows<D>(qtile, fr_base, i * 32, s), kf[s], sc);
-        dp = mfma16<F16>(frag_rows<D>(dtile, fr_base, i * 32, s), vf[s], dp);
+      for (int s0 = 0; s0 < NS; s0 += FB) {
+        bf16x8_t fq[FB], fd[FB];
+#pragma unroll
+        for (int s = 0; s < FB; ++s) {
+          fq[s] = frag_rows<D>(qtile, fr_base, i * 32, s0 + s);
+          fd[s] = frag_rows<D>(dtile, fr_base, i * 32, s0 + s);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < FB; ++s) {
+          sc = mfma16<F16>(fq[s], kf[s0 + s], sc);
+          dp = mfma16<F16>(fd[s], vf[s0 + s], dp);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // the first operands of the dV / dK products do not depend on the softmax: on their way during it
+      bf16x8_t td0[NT], tq0[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        td0[t] = frag_tr<D>(dtile, ft_base, i * 32, t);
+        tq0[t] = frag_tr<D>(qtile, ft_base, i * 32, t);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       const bool edge = wave_kv_edge || (qs + 32 > S) || (sh.causal && qs < wave_kv_min + 32);
       uint32_t keep = 0xffffu;
       if (DROP) keep = keep16_key_lane(sh.drop, head_blk, S >> 3, qs, kv_ld, lane, xch);
@@ -485,14 +554,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
       };
       if (edge) elements(std::true_type{});
       else elements(std::false_type{});
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const bf16x8_t pf = pack8<F16>(sc, h), dsf = pack8<F16>(dp, h);
+      {
+        const bf16x8_t pf0 = pack8<F16>(sc, 0), dsf0 = pack8<F16>(dp, 0), pf1 = pack8<F16>(sc, 1), dsf1 = pack8<F16>(dp, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8_t td1[NT], tq1[NT];   // second half's operands, requested in front of the first half's MFMAs
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-          dv[t] = mfma16<F16>(frag_tr<D>(dtile, ft_base, i * 32 + 16 * h, t), pf, dv[t]);
-          dk[t] = mfma16<F16>(frag_tr<D>(qtile, ft_base, i * 32 + 16 * h, t), dsf, dk[t]);
+          td1[t] = frag_tr<D>(dtile, ft_base, i * 32 + 16, t);
+          tq1[t] = frag_tr<D>(qtile, ft_base, i * 32 + 16, t);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          if constexpr (ACC_A) { mfma16_agpr<F16>(dv[t], td0[t], pf0); mfma16_agpr<F16>(dk[t], tq0[t], dsf0); }
+          else { dv[t] = mfma16<F16>(td0[t], pf0, dv[t]); dk[t] = mfma16<F16>(tq0[t], dsf0, dk[t]); }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          if constexpr (ACC_A) { mfma16_agpr<F16>(dv[t], td1[t], pf1); mfma16_agpr<F16>(dk[t], tq1[t], dsf1); }
+          else { dv[t] = mfma16<F16>(td1[t], pf1, dv[t]); dk[t] = mfma16<F16>(tq1[t], dsf1, dk[t]); }
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
@@ -513,6 +596,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
     }
   }
 
+  if (ACC_A) agpr_results_ready();
   if (my_kv < S) {
     bf16_t* krow = dqkv + ((int64_t)b * S + my_kv) * rs + H + a * D;
     bf16_t* vrow = krow + H;
@@ -544,7 +628,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
   constexpr int TE = Tile<D>::ELEMS;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int S = sh.seq, H = sh.hidden;
-  const BlockId blk = xcd_local_block();
+  const BlockId blk = xcd_local_block(sh.causal != 0);
   const int b = blk.b, a = blk.a, q_base = blk.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kc = lane >> 5;
   const int fr_base = rows_base<D>(lane), ft_base = tr_base<D>(lane);
@@ -812,7 +896,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_simple_kernel(AttnShape sh,
 // =================================== launchers ===================================================
 template <int D, bool F16>
 static void fwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens, void* out, float* lse, hipStream_t st) {
-  const size_t lds = (size_t)4 * Tile<D>::ELEMS * sizeof(bf16_t);
+  const size_t lds = (size_t)FWD_STAGES<D> * 2 * Tile<D>::ELEMS * sizeof(bf16_t);
   auto kern = s.drop.thr ? attn_fwd_bf16_kernel<D, true, F16> : attn_fwd_bf16_kernel<D, false, F16>;
   (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3((s.seq + 127) / 128, s.heads, s.batch), dim3(256), lds, st, s, (const bf16_t*)qkv,

@@ -133,6 +133,20 @@ __device__ __forceinline__ void buffer_load_lds_16(const void* base, unsigned by
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds, 16, voffset, soffset, 0, 0);
 }
 
+// Pipelines of direct loads wait for the oldest tile only: at most N vector-memory loads of this wavefront
+// still outstanding (they complete in issue order), LDS operations done; and a barrier that does not bring
+// the wait for ALL loads with it, as __syncthreads does.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_lds() {
+  static_assert(N >= 0 && N < 64, "six-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
+}
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 // Sum over the 64 lanes, returned to every lane. Data-parallel-primitive moves (quad permutes, mirrors inside
 // rows of 16 lanes, then the row broadcasts) keep the whole reduction in the vector ALU: six dependent adds
 // and one lane read instead of six round trips through the LDS crossbar.

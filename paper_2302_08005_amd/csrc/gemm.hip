@@ -89,8 +89,10 @@ __device__ __forceinline__ GateTerms gate_terms(float u, float w) {
 // 16 t of the stage, so that a slab can be brought in either through registers or by the direct
 // global -> LDS loads of gfx950 (one wave-level load fills 1 KB of consecutive LDS, lane l at byte 16 l).
 // Bank conflicts are avoided by permuting, inside each tile row, which 16-byte chunk of global memory a
-// thread fetches. The LDS serves 256 B per clock (64 banks of 4 B): 16 lanes of a 16-byte access, and 32
-// lanes of a transposing 8-byte read, are served together.
+// thread fetches. The LDS has 64 banks of 4 B: 16 lanes of a 16-byte access, and 32 lanes of a transposing
+// 8-byte read, are checked against each other for conflicts. Measured peak rates per CU with conflict-free
+// addresses and 8 or 16 wavefronts: 16-byte reads 257 B per clock, plain 8-byte reads 164, transposing
+// 8-byte reads 120 (about the same instruction rate as the 16-byte read, half the bytes).
 //  - K-contiguous tile [rows][BK]: position p of row r holds chunk p ^ swzK(r), swzK(r) = (r / RP) % (BK/8),
 //    RP = rows per 256 B. A fragment read (one chunk of 16 consecutive rows) then lands in 16 different
 //    16-byte bank groups. swzK depends on the lane only (wave tiles start at multiples of 32 rows), so a
@@ -104,15 +106,6 @@ __device__ __forceinline__ GateTerms gate_terms(float u, float w) {
 // Why direct loads: a ds_write moves 64 B per clock and keeps the LDS busy meanwhile, so writing a slab
 // costs as much LDS time as reading it three times; measured on the chip, fragment reads running beside
 // register-staged stores take the sum of both times, beside direct loads the maximum.
-template <int N>
-__device__ __forceinline__ void wait_loads_and_lds() {   // at most N vector-memory loads outstanding, LDS ops done
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
-}
-__device__ __forceinline__ void block_barrier() {        // barrier without the implied wait for all loads
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-}
 
 // PF: slabs of register prefetch of the register-staged path (NS == 0, two LDS stages).
 // NS: LDS stages of the direct-load path (0 = register-staged).
