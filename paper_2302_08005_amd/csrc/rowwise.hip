@@ -239,12 +239,12 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
 // columns of chunk c, for every row the block visits) and walk the block's rows R at a time; the two per-row
 // sums cross the wavefronts through LDS, one barrier per R rows, added in wave order; the column sums never
 // leave their lane, so no reduction over wavefronts is needed at the end.
-template <typename T, bool LN, int R>
-__global__ __launch_bounds__(512) void bdrln_bwd_wide_kernel(
+template <typename T, bool LN, int R, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void bdrln_bwd_wide_kernel(
     int64_t rows, int H, const T* __restrict__ dout, const T* __restrict__ z, const float* __restrict__ mu,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres_in,
     T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp, int dr_from_stored) {
-  __shared__ float xs[2][R][8][2];   // [parity][row][wave][s1, s2]
+  __shared__ float xs[2][R][MAXW][2];   // [parity][row][wave][s1, s2]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int c = threadIdx.x;
   const bool active = c < (H >> 3);
@@ -422,7 +422,11 @@ __global__ __launch_bounds__(256) void dropout_mask_kernel(int64_t nblocks8, uin
 
 // ---- host launchers -----------------------------------------------------------------------------
 
-static int nch_for(int H) { const int n = (H / 8 + 63) / 64; return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : n <= 5 ? 5 : 8; }
+// chunks of 8 columns per lane of the row-per-wavefront kernels (H <= 8192)
+static int nch_for(int H) {
+  const int n = (H / 8 + 63) / 64;
+  return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : n <= 5 ? 5 : n <= 8 ? 8 : n <= 10 ? 10 : 16;
+}
 
 template <typename T, bool BDR, bool LN>
 static void launch_fwd(int64_t rows, int H, const void* r, const void* bias, const void* res, const void* gamma,
@@ -440,7 +444,9 @@ static void launch_fwd(int64_t rows, int H, const void* r, const void* bias, con
     case 2: SLAPO_FWD(2); break;
     case 4: SLAPO_FWD(4); break;
     case 5: SLAPO_FWD(5); break;
-    default: SLAPO_FWD(8); break;
+    case 8: SLAPO_FWD(8); break;
+    case 10: SLAPO_FWD(10); break;
+    default: SLAPO_FWD(16); break;
   }
 #undef SLAPO_FWD
 }
@@ -468,11 +474,17 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
                        const void* gamma, const void* dres_in, void* dz_out, void* dr_out, float* partials,
                        const DropoutParams& dp, int dr_from_stored, hipStream_t st) {
   const int blocks = bdrln_bwd_blocks(rows);
-  if (H / 8 > 128) {   // wide rows: columns split over the wavefronts of a block (H <= 4096: at most 8 of them)
+  if (H / 8 > 128) {   // wide rows: columns split over the wavefronts of a block (at most 8 of them up to H = 4096,
+                       // 16 up to 8192: a kernel of its own, because the larger block halves the register budget)
     const int waves = (H / 8 + 63) / 64;
-    hipLaunchKernelGGL((bdrln_bwd_wide_kernel<T, LN, 4>), dim3(blocks), dim3(waves * 64), 0, st, rows, H, (const T*)dout,
-                       (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,
-                       dr_from_stored);
+    if (waves <= 8)
+      hipLaunchKernelGGL((bdrln_bwd_wide_kernel<T, LN, 4, 8>), dim3(blocks), dim3(waves * 64), 0, st, rows, H, (const T*)dout,
+                         (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,
+                         dr_from_stored);
+    else
+      hipLaunchKernelGGL((bdrln_bwd_wide_kernel<T, LN, 2, 16>), dim3(blocks), dim3(waves * 64), 0, st, rows, H, (const T*)dout,
+                         (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,
+                         dr_from_stored);
     return;
   }
 #define SLAPO_BWD(N, W)                                                                                      \

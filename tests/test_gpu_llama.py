@@ -190,8 +190,11 @@ def test_llama_layer_parity_full_size():
                   arch=W.LLAMA, config_id=41),
     W.LayerConfig("llama-three-tokens-bf16", 2, 3, 128, 1, 8, causal=1, dropout_p=0.1, dtype=W.BF16, pre_ln=1, ln_eps=1e-6,
                   arch=W.LLAMA, len_lo=1, len_hi=3, config_id=42),
+    # the widest rows the RMSNorm kernels take (narrow attention and FFN keep the oracle quick)
+    W.LayerConfig("llama-widest-hidden-bf16", 1, 72, 8192, 8, 256, causal=1, dropout_p=0.0, dtype=W.BF16, pre_ln=1, ln_eps=1e-6,
+                  arch=W.LLAMA, attn_dim=1024, config_id=43),
 ], ids=lambda c: c.name)
 def test_llama_layer_parity_degenerate_sizes(cfg):
-    errs, _, _ = run_case(cfg)
+    errs, _, _ = run_case(cfg, check_saved=cfg.hidden <= 4096)   # (intermediates: see the classic layer's test)
     bad = {k: v for k, v in errs.items() if not v <= TOL[cfg.dtype]}
     assert not bad, (bad, errs)

@@ -32,7 +32,7 @@ def _ref_fwd(r, bias, res, gamma, beta, keep, p, eps):
 
 
 @pytest.mark.parametrize("dtype", [W.FP32, W.BF16, W.FP16])
-@pytest.mark.parametrize("T,H", [(37, 256), (515, 1024), (130, 2560), (64, 4096), (9, 64)])
+@pytest.mark.parametrize("T,H", [(37, 256), (515, 1024), (130, 2560), (64, 4096), (9, 64), (70, 5120), (35, 8192)])
 def test_bdrln_forward_and_backward(dtype, T, H):
     rng = np.random.default_rng(T * 7 + H)
     p, seed, site, layer = 0.1, 11, 1, 5
