@@ -410,6 +410,12 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(AttnShape sh, const T* 
 }
 
 // ============================ backward: dK, dV per key tile ======================================
+// LDS stages of the dK/dV kernel's Q/dO ring. Two: 128-wide heads run one workgroup per CU whatever the LDS
+// footprint (registers), so more stages would be free there, but three and four were measured equal to two
+// (the 1300-2600 cycles a tile step spends outside its ~4100 cycles of compute are the wavefronts waiting
+// for each other at the barrier, not for the next tile).
+template <int D> constexpr int DKDV_STAGES = 2;
+
 template <int D, bool DROP, bool F16>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, const bf16_t* __restrict__ qkv,
                                                                  const int32_t* __restrict__ seqlens,
@@ -421,7 +427,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
   constexpr int TE = Tile<D>::ELEMS;
   constexpr int STAGE = 2 * TE + 256;   // bf16 units: Q tile, dO tile, 64 lse + 64 delta floats
   constexpr int FB = 4;                 // k-steps of fragment prefetch (register budget: 8 FB registers)
+  constexpr int NSTG = DKDV_STAGES<D>;
   constexpr bool ACC_A = (D == 128);    // dK/dV accumulators in AGPRs (see mfma16_agpr)
+  constexpr bool PIPE = ACC_A && !DROP; // hand-pipelined sub-tiles for tiles without a mask boundary (see compute)
+  static_assert(!PIPE || (NS == 8 && NT == 4), "the pipelined rounds are written for D = 128");
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int S = sh.seq, H = sh.hidden;
   const BlockId blk = xcd_local_block();
@@ -440,7 +449,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
   const bool wave_kv_edge = wave_kv_min + 32 > kv_len;   // some of this wave's keys are hidden
   // DROP: block index of (query 0, key 0) of this head, and this wavefront's exchange area behind the stages
   const uint64_t head_blk = ((((uint64_t)b * sh.heads + a) * S) * (uint64_t)S) >> 3;
-  uint32_t* xch = reinterpret_cast<uint32_t*>(smem + 2 * STAGE) + wave * 512;
+  uint32_t* xch = reinterpret_cast<uint32_t*>(smem + DKDV_STAGES<D> * STAGE) + wave * 512;
   const float scale = rsqrtf((float)D), sl2 = LOG2E * scale;
 
   bf16x8_t kf[NS], vf[NS];
@@ -485,6 +494,125 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
     const bf16_t* qtile = smem + stage * STAGE;
     const bf16_t* dtile = qtile + TE;
     const float* stats = reinterpret_cast<const float*>(qtile + 2 * TE);
+    if constexpr (PIPE) {
+      // One wavefront per SIMD (128-wide heads): nothing else runs while this wavefront does the softmax
+      // arithmetic of a sub-tile, so for tiles without a mask boundary the two sub-tiles are software-
+      // pipelined by hand: every MFMA is followed by the vector work of one score element of the OTHER
+      // sub-tile, which issues while the matrix core is busy.
+      //   scores(0);  scores(1) || softmax(0);  dV,dK(0) || softmax(1);  dV,dK(1)
+      const bool interior = !wave_kv_edge && q0 + 64 <= S && !(sh.causal && q0 < wave_kv_min + 32);
+      if (interior) {
+        f32x16_t sc0, dp0, sc1, dp1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc0[r] = dp0[r] = sc1[r] = dp1[r] = 0.f;
+        auto element = [&](f32x16_t& sc, f32x16_t& dp, int r, float ls, float ds) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -ls));
+          sc[r] = p;
+          dp[r] = p * (dp[r] - ds);
+        };
+        // scores of sub-tile 0
+#pragma unroll
+        for (int s0 = 0; s0 < NS; s0 += FB) {
+          bf16x8_t fq[FB], fd[FB];
+#pragma unroll
+          for (int s = 0; s < FB; ++s) {
+            fq[s] = frag_rows<D>(qtile, fr_base, 0, s0 + s);
+            fd[s] = frag_rows<D>(dtile, fr_base, 0, s0 + s);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int s = 0; s < FB; ++s) {
+            sc0 = mfma16<F16>(fq[s], kf[s0 + s], sc0);
+            dp0 = mfma16<F16>(fd[s], vf[s0 + s], dp0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // scores of sub-tile 1 (two k-steps = four MFMAs per round) || softmax of sub-tile 0 (four elements per round)
+        {
+          bf16x8_t fq[2][2], fd[2][2];
+#pragma unroll
+          for (int k = 0; k < 2; ++k) { fq[0][k] = frag_rows<D>(qtile, fr_base, 32, k); fd[0][k] = frag_rows<D>(dtile, fr_base, 32, k); }
+#pragma unroll
+          for (int g = 0; g < NS / 2; ++g) {
+            const int cur = g & 1;
+            if (g + 1 < NS / 2) {
+#pragma unroll
+              for (int k = 0; k < 2; ++k) {
+                fq[cur ^ 1][k] = frag_rows<D>(qtile, fr_base, 32, 2 * g + 2 + k);
+                fd[cur ^ 1][k] = frag_rows<D>(dtile, fr_base, 32, 2 * g + 2 + k);
+              }
+            }
+            const float4 l4 = *reinterpret_cast<const float4*>(stats + g * 8 + 4 * kc);
+            const float4 d4 = *reinterpret_cast<const float4*>(stats + 64 + g * 8 + 4 * kc);
+            __builtin_amdgcn_sched_barrier(0);
+            sc1 = mfma16<F16>(fq[cur][0], kf[2 * g], sc1);
+            element(sc0, dp0, 4 * g + 0, l4.x, d4.x);
+            __builtin_amdgcn_sched_barrier(0);
+            dp1 = mfma16<F16>(fd[cur][0], vf[2 * g], dp1);
+            element(sc0, dp0, 4 * g + 1, l4.y, d4.y);
+            __builtin_amdgcn_sched_barrier(0);
+            sc1 = mfma16<F16>(fq[cur][1], kf[2 * g + 1], sc1);
+            element(sc0, dp0, 4 * g + 2, l4.z, d4.z);
+            __builtin_amdgcn_sched_barrier(0);
+            dp1 = mfma16<F16>(fd[cur][1], vf[2 * g + 1], dp1);
+            element(sc0, dp0, 4 * g + 3, l4.w, d4.w);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        // dV, dK of sub-tile 0 (four MFMAs per round) || softmax of sub-tile 1
+        {
+          const bf16x8_t pf[2] = {pack8<F16>(sc0, 0), pack8<F16>(sc0, 1)}, dsf[2] = {pack8<F16>(dp0, 0), pack8<F16>(dp0, 1)};
+          bf16x8_t td[2][2], tq[2][2];   // [round parity][column block of the round]
+#pragma unroll
+          for (int k = 0; k < 2; ++k) { td[0][k] = frag_tr<D>(dtile, ft_base, 0, k); tq[0][k] = frag_tr<D>(qtile, ft_base, 0, k); }
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {   // round g: half h = g / 2, column blocks t = 2 (g % 2), 2 (g % 2) + 1
+            const int cur = g & 1, h = g >> 1, t0 = 2 * (g & 1);
+            if (g + 1 < 4) {
+              const int hn = (g + 1) >> 1, tn = 2 * ((g + 1) & 1);
+#pragma unroll
+              for (int k = 0; k < 2; ++k) {
+                td[cur ^ 1][k] = frag_tr<D>(dtile, ft_base, 16 * hn, tn + k);
+                tq[cur ^ 1][k] = frag_tr<D>(qtile, ft_base, 16 * hn, tn + k);
+              }
+            }
+            const float4 l4 = *reinterpret_cast<const float4*>(stats + 32 + g * 8 + 4 * kc);
+            const float4 d4 = *reinterpret_cast<const float4*>(stats + 64 + 32 + g * 8 + 4 * kc);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma16_agpr<F16>(dv[t0], td[cur][0], pf[h]);
+            element(sc1, dp1, 4 * g + 0, l4.x, d4.x);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma16_agpr<F16>(dk[t0], tq[cur][0], dsf[h]);
+            element(sc1, dp1, 4 * g + 1, l4.y, d4.y);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma16_agpr<F16>(dv[t0 + 1], td[cur][1], pf[h]);
+            element(sc1, dp1, 4 * g + 2, l4.z, d4.z);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma16_agpr<F16>(dk[t0 + 1], tq[cur][1], dsf[h]);
+            element(sc1, dp1, 4 * g + 3, l4.w, d4.w);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        // dV, dK of sub-tile 1
+        {
+          const bf16x8_t pf[2] = {pack8<F16>(sc1, 0), pack8<F16>(sc1, 1)}, dsf[2] = {pack8<F16>(dp1, 0), pack8<F16>(dp1, 1)};
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            bf16x8_t td[NT], tq[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+              td[t] = frag_tr<D>(dtile, ft_base, 32 + 16 * h, t);
+              tq[t] = frag_tr<D>(qtile, ft_base, 32 + 16 * h, t);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) { mfma16_agpr<F16>(dv[t], td[t], pf[h]); mfma16_agpr<F16>(dk[t], tq[t], dsf[h]); }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        return;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int qs = q0 + i * 32;
@@ -579,20 +707,34 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
       }
     }
   };
+  // Ring of NSTG stages: tile it + NSTG - 1 is requested while tile it is computed; the statistics of tile
+  // it + 1 travel through a register and are requested BEFORE that step's tile loads, so that waiting for
+  // them (loads complete in issue order) leaves the younger tile loads in flight. LPT = tile loads per step
+  // that every wavefront issues at the least.
   if (n_tiles > 0) {
-    issue_tile(0, 0);
-    store_stats(0, load_stats(q_first * 64));
-    __syncthreads();   // (waits for this wavefront's loads, then for everybody's)
+    constexpr int LPT = 2 * TileDirect<D>::LEAST;
+    const float stat0 = load_stats(q_first * 64);
+#pragma unroll
+    for (int t = 0; t < NSTG - 1; ++t)
+      if (t < n_tiles) issue_tile(t, t);
+    store_stats(0, stat0);
+    if (n_tiles >= NSTG - 1) wait_loads_and_lds<(NSTG - 2) * LPT>();
+    else wait_loads_and_lds<0>();
+    block_barrier();
+    int stage = 0, fill = NSTG - 1;
     for (int it = 0; it < n_tiles; ++it) {
-      const bool more = it + 1 < n_tiles;
+      const bool more = it + 1 < n_tiles, far = it + NSTG - 1 < n_tiles;
+      const int next = stage + 1 == NSTG ? 0 : stage + 1;
       float next_stat = 0.f;
-      if (more) {   // that stage was last read before the barrier above
-        issue_tile((it + 1) & 1, it + 1);
-        next_stat = load_stats((q_first + it + 1) * 64);
-      }
-      compute(it & 1, it);
-      if (more) store_stats((it + 1) & 1, next_stat);
-      __syncthreads();
+      if (more) next_stat = load_stats((q_first + it + 1) * 64);
+      if (far) issue_tile(fill, it + NSTG - 1);   // that stage was last read before the barrier that ended step it - 1
+      compute(stage, it);
+      if (more) store_stats(next, next_stat);
+      if (far) wait_loads_and_lds<(NSTG - 2) * LPT>();
+      else wait_loads_and_lds<0>();
+      block_barrier();
+      stage = next;
+      fill = fill + 1 == NSTG ? 0 : fill + 1;
     }
   }
 
@@ -932,7 +1074,7 @@ static void bwd_bf16(const AttnShape& s, const void* qkv, const int32_t* seqlens
   }
   {
     // with dropout: 2 KB per wavefront behind the stages for the exchange of mask draws
-    const size_t lds = (size_t)2 * (2 * Tile<D>::ELEMS + 256) * sizeof(bf16_t) + (s.drop.thr ? 4 * 2048 : 0);
+    const size_t lds = (size_t)DKDV_STAGES<D> * (2 * Tile<D>::ELEMS + 256) * sizeof(bf16_t) + (s.drop.thr ? 4 * 2048 : 0);
     auto kern = s.drop.thr ? attn_bwd_dkdv_bf16_kernel<D, true, F16> : attn_bwd_dkdv_bf16_kernel<D, false, F16>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, (const bf16_t*)qkv, seqlens, (const bf16_t*)dout, lse,
