@@ -18,6 +18,10 @@ CASES = [
     (2, 256, 3, 64, 1, [256, 77], 8.0),       # causal + padding, large scores (online-softmax rescaling)
     (1, 384, 2, 128, 1, None, 1.0),
     (2, 136, 1, 128, 0, [100, 136], 4.0),
+    # d = 128 with mask-free and boundary tiles side by side (the dK/dV kernel pipelines the mask-free ones by hand):
+    # ragged length, causal + padding; and a bidirectional one whose tiles are all mask-free
+    (2, 456, 2, 128, 1, [456, 300], 2.0),
+    (2, 320, 1, 128, 0, None, 1.0),
     # with dropout on the attention probabilities (last entry): plain, causal + padding, d = 128 causal, padding
     (2, 128, 2, 64, 0, None, 1.0, 0.2),
     (2, 256, 3, 64, 1, [256, 77], 4.0, 0.1),
