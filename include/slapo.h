@@ -42,7 +42,7 @@ typedef enum {
   SLAPO_OK = 0,
   SLAPO_ERR_NULL = -1,        /* a required pointer is NULL                                   */
   SLAPO_ERR_SHAPE = -2,       /* non-positive size, hidden % heads != 0, dropout_p not in [0,1) */
-  SLAPO_ERR_UNSUPPORTED = -3, /* head dim not 64/128, hidden > 8192, unknown enum value        */
+  SLAPO_ERR_UNSUPPORTED = -3, /* head dim not 64/128, hidden > 8192, fp32 seq limit, bad enum  */
   SLAPO_ERR_ALIGN = -4,       /* pointer not 16-byte aligned / size not a multiple of 8        */
   SLAPO_ERR_WORKSPACE = -5,   /* reserved                                                      */
   SLAPO_ERR_HIP = -6          /* a kernel launch reported an error                             */
@@ -59,7 +59,7 @@ enum { SLAPO_GELU_ERF = 0, SLAPO_RELU = 1 };
 enum { SLAPO_ARCH_CLASSIC = 0, SLAPO_ARCH_LLAMA = 1 };
 
 /* Layer description (host struct). The head dim (hidden/heads, or attn_dim/heads) must be 64 or 128; hidden,
- * ffn multiples of 8; hidden <= 8192. */
+ * ffn multiples of 8; hidden <= 8192; in the fp32 mode seq <= 5056 (d = 64) / 4992 (d = 128). */
 typedef struct {
   int32_t batch, seq, hidden, heads, ffn;
   int32_t causal;           /* 1: query i sees keys j <= i                                     */

@@ -28,6 +28,8 @@ int check_desc(const slapo_layer_desc* d) {
   const int hd = attn_width(d) / d->heads;
   if (hd != 64 && hd != 128) return SLAPO_ERR_UNSUPPORTED;
   if (d->hidden > 8192) return SLAPO_ERR_UNSUPPORTED;   // the row kernels hold a row per wavefront / per block
+  // the fp32 (correctness-mode) attention keeps two score rows per wavefront in LDS: 16 (2 d + 2 seq) bytes per block
+  if (d->dtype == SLAPO_FP32 && (int64_t)16 * (2 * hd + 2 * (int64_t)d->seq) > 160 * 1024) return SLAPO_ERR_UNSUPPORTED;
   if (d->dtype != SLAPO_BF16 && d->dtype != SLAPO_FP32 && d->dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (d->act != SLAPO_GELU_ERF && d->act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
   if ((d->causal != 0 && d->causal != 1) || (d->pre_ln != 0 && d->pre_ln != 1)) return SLAPO_ERR_UNSUPPORTED;

@@ -30,7 +30,7 @@ def test_descriptor_validation():
     assert ck_saved == 0 and scratch + saved <= ck_scratch <= scratch + saved + 256   # the activations move into scratch
     bad = [
         (dict(checkpoint=2), -3), (dict(heads=5), -2), (dict(batch=0), -2), (dict(dropout_p=1.0), -2), (dict(dropout_p=-0.1), -2),
-        (dict(hidden=256, heads=8), -3), (dict(hidden=16384, heads=128), -3), (dict(dtype=7), -3), (dict(act=3), -3),
+        (dict(hidden=256, heads=8), -3), (dict(hidden=16384, heads=128), -3), (dict(dtype=B.FP32, seq=5120), -3), (dict(dtype=7), -3), (dict(act=3), -3),
         (dict(ffn=1001), -4), (dict(ln_eps=0.0), -2),
     ]
     for kw, code in bad:

@@ -22,6 +22,8 @@ CASES = [
     # ragged length, causal + padding; and a bidirectional one whose tiles are all mask-free
     (2, 456, 2, 128, 1, [456, 300], 2.0),
     (2, 320, 1, 128, 0, None, 1.0),
+    # a long sequence (65 key tiles), ragged, causal + padding
+    (1, 4160, 1, 64, 1, [3000], 1.0),
     # with dropout on the attention probabilities (last entry): plain, causal + padding, d = 128 causal, padding
     (2, 128, 2, 64, 0, None, 1.0, 0.2),
     (2, 256, 3, 64, 1, [256, 77], 4.0, 0.1),
