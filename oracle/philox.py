@@ -9,7 +9,8 @@ independent implementation can regenerate it.
   element index  e = t*H + c                      (row-major position in the [T, H] tensor)
   counter        (lo32(e>>3), hi32(e>>3), site, layer_id),  key (lo32(seed), hi32(seed))
   16-bit draw    r16 = (out[(e & 7) >> 1] >> (16 * (e & 1))) & 0xffff
-  keep           r16 >= thr,  thr = round(p * 65536)
+  keep           r16 >= thr,  thr = p * 65536 rounded to the nearest integer, halves away from zero, with p
+                 the probability as the single-precision number the layer descriptor carries
 
 All arithmetic is done on numpy uint64 arrays holding 32-bit quantities.
 """
@@ -40,7 +41,10 @@ def philox4x32_10(c0, c1, c2, c3, k0, k1):
 
 
 def dropout_threshold(p: float) -> int:
-    return int(round(float(p) * 65536.0))
+    """16-bit threshold of a drop probability. The probability travels in a single-precision descriptor field,
+    so it is rounded to single precision first; its product with 2^16 is then exact in double precision and is
+    rounded to the nearest integer with halves going up (p >= 0, so up is away from zero)."""
+    return int(np.floor(float(np.float32(p)) * 65536.0 + 0.5))
 
 
 def keep_mask(n_elements: int, p: float, seed: int, site: int, layer_id: int) -> np.ndarray:

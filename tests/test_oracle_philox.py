@@ -54,7 +54,10 @@ def _keep_scalar(e, p, seed, site, layer_id):
     blk = e >> 3
     o = _philox_int([blk % 2**32, blk >> 32, site, layer_id], [seed % 2**32, seed >> 32])
     r16 = (o[(e & 7) >> 1] >> (16 * (e & 1))) & 0xFFFF
-    return r16 >= int(round(p * 65536.0))
+    from fractions import Fraction
+    import math
+    thr = math.floor(Fraction(float(np.float32(p))) * 65536 + Fraction(1, 2))   # exact rational arithmetic
+    return r16 >= thr
 
 
 def test_mask_element_mapping():
@@ -90,3 +93,19 @@ def test_mask_statistics_and_independence():
 def pytest_approx(v, tol):
     import pytest
     return pytest.approx(v, abs=tol)
+
+
+def test_threshold_rounding():
+    """The threshold is round-half-away-from-zero of the SINGLE-precision probability times 2^16 (values by hand)."""
+    assert philox.dropout_threshold(0.0) == 0
+    assert philox.dropout_threshold(0.1) == 6554          # 6553.6
+    assert philox.dropout_threshold(0.5) == 32768
+    assert philox.dropout_threshold(0.25 + 2.0 ** -17) == 16385     # exactly 16384.5: the half goes up, not to even
+    assert philox.dropout_threshold(0.25 + 3 * 2.0 ** -17) == 16386  # exactly 16385.5: up as well
+    # 13107 * 2^-17 = 6553.5 / 65536 is a single-precision number; a double a hair below it rounds to it first
+    assert philox.dropout_threshold(13107 * 2.0 ** -17 - 1e-12) == 6554
+    # and the mask follows the threshold: a draw equal to the threshold is kept, one below is dropped
+    thr = philox.dropout_threshold(0.25 + 2.0 ** -17)
+    m_lo = philox.keep_mask(1 << 16, 0.25, 9, 0, 0)
+    m_hi = philox.keep_mask(1 << 16, 0.25 + 2.0 ** -17, 9, 0, 0)
+    assert thr == philox.dropout_threshold(0.25) + 1 and (m_lo | ~m_hi).all() and m_lo.sum() >= m_hi.sum()
