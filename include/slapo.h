@@ -20,8 +20,18 @@
  *     no device memory is allocated or freed, no pointer is kept after the call returns.
  *     slapo_layer_bwd issues its weight-gradient GEMMs on one internal helper stream per device, created
  *     on first use and kept for the life of the process, forked from and joined back into `stream` with
- *     events (capturable in a HIP graph like any fork/join); SLAPO_SINGLE_STREAM=1 in the environment
- *     keeps everything on `stream` (and SLAPO_NO_SPLITK=1 turns the K-range weight gradients off: A/B timing). This helper stream is the only state the library holds.
+ *     events (capturable in a HIP graph like any fork/join). This helper stream and its events are the only
+ *     state the library holds.
+ *   - Threads: every entry point may be called from several host threads at once, also on one device; calls
+ *     touch only their own arguments. Backward calls of different threads on the same device share that
+ *     device's helper stream: each event record and the stream wait that consumes it are issued under a
+ *     per-device lock, so every call waits for its own records, and the weight-gradient work of concurrent
+ *     calls queues up on the one helper stream in issue order (correct, but not concurrent with each other).
+ *     Two calls that are given the same `scratch` or `saved` buffer must be ordered by the caller as usual.
+ *   - SLAPO_DEBUG in the environment, read once at first use, is a comma-separated list of debugging / A-B
+ *     timing switches: "single-stream" keeps all of backward on `stream`; "no-splitk" computes every weight
+ *     gradient as one plain GEMM (and shrinks the workspace sizes reported accordingly). Nothing else in the
+ *     environment changes what the library does.
  *   - Return value: SLAPO_OK (0) or a negative slapo_status. Argument checks run before the first
  *     HIP call, so they behave the same on a host without a GPU. Nothing throws or aborts.
  *   - Same inputs and seed give bitwise identical outputs (no floating-point atomics anywhere).
@@ -44,7 +54,7 @@ typedef enum {
   SLAPO_ERR_SHAPE = -2,       /* non-positive size, hidden % heads != 0, dropout_p not in [0,1) */
   SLAPO_ERR_UNSUPPORTED = -3, /* head dim not 64/128, hidden > 8192, fp32 seq limit, bad enum  */
   SLAPO_ERR_ALIGN = -4,       /* pointer not 16-byte aligned / size not a multiple of 8        */
-  SLAPO_ERR_WORKSPACE = -5,   /* reserved                                                      */
+  SLAPO_ERR_WORKSPACE = -5,   /* the shape needs more workspace than a fixed-size buffer of the library holds */
   SLAPO_ERR_HIP = -6          /* a kernel launch reported an error                             */
 } slapo_status;
 
@@ -72,8 +82,8 @@ typedef struct {
   int32_t layer_id;         /* mixed into the dropout counter so stacked layers differ         */
   float ln_eps;             /* LayerNorm epsilon (inside the square root)                      */
   int32_t accumulate_grads; /* 0: overwrite parameter gradients, 1: add to them                */
-  int32_t checkpoint;       /* 1: activation checkpointing (section 2.2: "the effective activation
-                               checkpointing"): forward keeps nothing, backward recomputes the
+  int32_t checkpoint;       /* 1: activation checkpointing (the third optimisation the paper's schedules apply,
+                               section 2.2): forward keeps nothing, backward recomputes the
                                forward from x first. No `saved` buffer exists (size 0, the argument is
                                ignored and may be NULL); `scratch` is larger instead. The regenerated
                                dropout masks make the recomputation exact: gradients are bit for bit

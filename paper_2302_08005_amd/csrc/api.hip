@@ -62,6 +62,29 @@ int check_tables(const slapo_layer_desc* d, const void* const (&ps)[12]) {
   return SLAPO_OK;
 }
 
+}  // namespace
+
+namespace slapo {
+// SLAPO_DEBUG in the environment: a comma-separated list of switches for debugging and A/B timing, read once.
+//   single-stream  backward keeps all of its work on the caller's stream (no helper stream)
+//   no-splitk      weight gradients always run as one plain GEMM (no K ranges; also shrinks the workspace sizes
+//                  the *_workspace calls report, so set it before the first call, not between size query and use)
+bool debug_flag(const char* name) {
+  const char* env = getenv("SLAPO_DEBUG");
+  if (!env) return false;
+  const size_t n = strlen(name);
+  for (const char* p = env; *p;) {
+    const char* e = strchr(p, ',');
+    const size_t len = e ? (size_t)(e - p) : strlen(p);
+    if (len == n && !strncmp(p, name, n)) return true;
+    p += len + (e ? 1 : 0);
+  }
+  return false;
+}
+}  // namespace slapo
+
+namespace {
+
 DropoutParams make_dropout(const slapo_layer_desc* d, int site) {
   DropoutParams dp;
   dp.key0 = (uint32_t)(d->seed & 0xffffffffu);
@@ -84,24 +107,43 @@ AttnShape make_attn_shape(const slapo_layer_desc* d) {
   return as;
 }
 
-int finish() { return hipGetLastError() == hipSuccess ? SLAPO_OK : SLAPO_ERR_HIP; }
+// A launch that failed leaves its error in the runtime's per-thread "last error". Every entry point samples that
+// slot before its first launch (entry_error) and again after its last one (finish): an error that was already
+// there belongs to somebody else and is neither reported as ours nor cleared; one that appeared in between is
+// ours, is reported as SLAPO_ERR_HIP and cleared.
+thread_local hipError_t g_error_at_entry = hipSuccess;
+void entry_error() { g_error_at_entry = hipPeekAtLastError(); }
+int finish() {
+  if (g_error_at_entry != hipSuccess) return SLAPO_OK;   // cannot tell ours from the stale one: leave it to its owner
+  return hipGetLastError() == hipSuccess ? SLAPO_OK : SLAPO_ERR_HIP;
+}
 
 // The weight-gradient GEMMs of the backward pass do not feed the data-gradient chain, and most kernels of
 // the chain leave half of each CU's LDS and wave slots free (one 128x128 tile per CU). They are therefore
 // issued on a helper stream that forks from and joins back into the caller's stream with events, so the
 // two kinds of GEMM share the CUs. One helper stream and a few events per device are created on first use
-// and kept for the life of the process (the only state the library holds). SLAPO_SINGLE_STREAM=1 in the
-// environment turns this off (debugging / A-B timing).
+// and kept for the life of the process (the only state the library holds). Host threads that call into the
+// library on the same device share them: every event record and the stream wait that consumes it are issued
+// under the device's mutex, so a wait always captures the record of its own call (a wait refers to the
+// record that precedes it at the time it is issued), and the calls' helper-stream work simply queues up
+// behind each other. "single-stream" in SLAPO_DEBUG turns the helper stream off.
 struct SideStream {
   hipStream_t stream = nullptr;
   hipEvent_t fork[4] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t join = nullptr;
   int state = 0;   // 0 untried, 1 ready, -1 unavailable
+  std::mutex pair_mu;   // held across each (record, wait) pair
+  // everything issued on `from` so far happens before what is issued on `to` from now on
+  void order(hipEvent_t ev, hipStream_t from, hipStream_t to) {
+    std::lock_guard<std::mutex> lock(pair_mu);
+    (void)hipEventRecord(ev, from);
+    (void)hipStreamWaitEvent(to, ev, 0);
+  }
 };
 SideStream* side_stream() {
   static SideStream table[16];
   static std::mutex mu;
-  static const bool disabled = getenv("SLAPO_SINGLE_STREAM") && atoi(getenv("SLAPO_SINGLE_STREAM")) != 0;
+  static const bool disabled = debug_flag("single-stream");
   if (disabled) return nullptr;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
@@ -198,7 +240,7 @@ const char* slapo_status_string(int status) {
     case SLAPO_ERR_SHAPE: return "invalid shape or scalar argument";
     case SLAPO_ERR_UNSUPPORTED: return "unsupported configuration";
     case SLAPO_ERR_ALIGN: return "pointer not 16-byte aligned or size not a multiple of 8";
-    case SLAPO_ERR_WORKSPACE: return "workspace too small";
+    case SLAPO_ERR_WORKSPACE: return "shape needs more workspace than the library's fixed-size buffer holds";
     case SLAPO_ERR_HIP: return "HIP reported an error";
     default: return "unknown status";
   }
@@ -331,6 +373,7 @@ int slapo_layer_fwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
                     void* y, void* saved, void* scratch, void* stream) {
   const int rc = check_forward_args(d, p, x, y, saved, scratch);
   if (rc) return rc;
+  entry_error();
   if (d->checkpoint) saved = (char*)scratch + scratch_layout(d).acts;   // transient: nothing is kept for backward
   run_forward(d, p, x, seqlens, y, saved, scratch, (hipStream_t)stream);
   return finish();
@@ -391,7 +434,7 @@ static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   const bool solo = side == nullptr;   // one stream: every GEMM has the chip to itself
   hipStream_t ws = side ? side->stream : st;
   auto fork = [&](int i) {   // everything issued on st so far happens before what follows on ws
-    if (side) { (void)hipEventRecord(side->fork[i], st); (void)hipStreamWaitEvent(ws, side->fork[i], 0); }
+    if (side) side->order(side->fork[i], st, ws);
   };
   // weight gradient: C (+)= A^T B
   float* splitk_ws = W.splitk ? (float*)(sc + W.splitk) : nullptr;
@@ -478,10 +521,7 @@ static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   // the last bias gradient goes behind the data gradient on the caller's stream: the helper stream's last
   // product is the longer one, and this way the two streams end at about the same time
   if (!llama) colsum(dqkv, 3 * A, gr->bqkv, st);
-  if (side) {   // join: the caller's stream continues only after the weight gradients are complete
-    (void)hipEventRecord(side->join, ws);
-    (void)hipStreamWaitEvent(st, side->join, 0);
-  }
+  if (side) side->order(side->join, ws, st);   // join: the caller's stream continues only after the weight gradients are complete
   return finish();
 }
 
@@ -490,6 +530,7 @@ int slapo_layer_bwd(const slapo_layer_desc* d, const slapo_layer_params* p, cons
                     void* stream) {
   const int rc = check_backward_args(d, p, x, dy, saved, dx, gr, scratch);
   if (rc) return rc;
+  entry_error();
   return run_backward(d, p, x, seqlens, dy, saved, dx, gr, scratch, (hipStream_t)stream);
 }
 
@@ -526,6 +567,7 @@ int slapo_stack_fwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
     void* out = l == n_layers - 1 ? y : (char*)acts + (size_t)l * ab;
     if ((rc = check_forward_args(&d, params + l, in, out, saved, scratch))) return rc;
   }
+  entry_error();
   // with checkpointing every layer works in the same transient region, whose contents die with the layer
   char* transient = (char*)scratch + scratch_layout(desc).acts;
   auto saved_of = [&](int l) -> void* { return desc->checkpoint ? transient : (char*)saved + (size_t)l * sb; };
@@ -559,6 +601,7 @@ int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
     const void* in = l == 0 ? x : (const char*)acts + (size_t)(l - 1) * ab;
     if ((rc = check_backward_args(&d, params + l, in, dy, saved, dx, grads + l, scratch))) return rc;
   }
+  entry_error();
   const void* gin = dy;
   for (int l = n_layers - 1; l >= 0; --l) {
     d.layer_id = desc->layer_id + l;
@@ -601,6 +644,7 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
   if (layout == GEMM_TN ? (M % 8) : (K % 8)) return SLAPO_ERR_ALIGN;   // A's contiguous dimension
   if (layout == GEMM_NT && (K % 8)) return SLAPO_ERR_ALIGN;
   if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
+  entry_error();
   launch_gemm(dtype, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
               (hipStream_t)stream, true);
   return finish();
@@ -629,6 +673,7 @@ int slapo_weight_grad(int dtype, int accumulate, int64_t M, int64_t N, int64_t K
   if (!A || !B || !C) return SLAPO_ERR_NULL;
   if (!ws && weight_grad_ws_bytes(dtype, (int)M, (int)N, (int)K)) return SLAPO_ERR_NULL;
   if (misaligned(A) || misaligned(B) || misaligned(C) || misaligned(ws)) return SLAPO_ERR_ALIGN;
+  entry_error();
   launch_weight_grad(dtype, accumulate ? 1 : 0, (int)M, (int)N, (int)K, A, B, C, (float*)ws, (hipStream_t)stream);
   return finish();
 }
@@ -640,6 +685,7 @@ int slapo_attn_fwd(const slapo_layer_desc* d, const void* qkv, const int32_t* se
   if (!qkv || !out || !lse) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(out)) return SLAPO_ERR_ALIGN;
   const AttnShape as = make_attn_shape(d);
+  entry_error();
   launch_attn_fwd(d->dtype, as, qkv, seqlens, out, lse, (hipStream_t)stream);
   return finish();
 }
@@ -651,6 +697,7 @@ int slapo_attn_bwd(const slapo_layer_desc* d, const void* qkv, const int32_t* se
   if (!qkv || !out || !dout || !lse || !delta || !dqkv) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(out) || misaligned(dout) || misaligned(dqkv)) return SLAPO_ERR_ALIGN;
   const AttnShape as = make_attn_shape(d);
+  entry_error();
   launch_attn_bwd(d->dtype, as, qkv, seqlens, out, dout, lse, delta, dqkv, (hipStream_t)stream);
   return finish();
 }
@@ -668,6 +715,7 @@ int slapo_bdrln_fwd(const slapo_layer_desc* d, int site, int64_t T, const void* 
   if (!r && !gamma) return SLAPO_ERR_NULL;
   if (misaligned(r) || misaligned(bias) || misaligned(res) || misaligned(gamma) || misaligned(beta) ||
       misaligned(z_out) || misaligned(out)) return SLAPO_ERR_ALIGN;
+  entry_error();
   launch_bdrln_fwd(d->dtype, T, d->hidden, r, bias, res, gamma, beta, z_out, out, mu, rstd,
                    make_dropout(d, site), d->ln_eps, llama ? 1 : 0, (hipStream_t)stream);
   return finish();
@@ -686,6 +734,7 @@ int slapo_bdrln_bwd(const slapo_layer_desc* d, int site, int64_t T, const void* 
   if (!dz_out && !dr_out) return SLAPO_ERR_NULL;
   if (misaligned(dout) || misaligned(z) || misaligned(gamma) || misaligned(dres_in) || misaligned(dz_out) ||
       misaligned(dr_out) || misaligned(partials)) return SLAPO_ERR_ALIGN;
+  entry_error();
   launch_bdrln_bwd(d->dtype, T, d->hidden, dout, z, mu, rstd, gamma, dres_in, dz_out, dr_out, partials,
                    make_dropout(d, site), is_llama(d) ? 1 : 0, (hipStream_t)stream);
   return finish();
@@ -698,6 +747,7 @@ int slapo_rope(const slapo_layer_desc* d, void* qkv, float* table, int inverse, 
   if (!qkv || !table) return SLAPO_ERR_NULL;
   if (misaligned(qkv) || misaligned(table)) return SLAPO_ERR_ALIGN;
   const int hd = attn_width(d) / d->heads;
+  entry_error();
   launch_rope_table(d->seq, hd, d->rope_base, table, (hipStream_t)stream);
   launch_rope(d->dtype, (int64_t)d->batch * d->seq, d->seq, attn_width(d), hd, table, qkv, inverse ? 1 : 0, (hipStream_t)stream);
   return finish();
@@ -710,6 +760,7 @@ int slapo_colsum_partials(int dtype, int64_t T, int64_t N, const void* a, float*
   if (T <= 0 || N <= 0) return SLAPO_ERR_SHAPE;
   if (!a || !partials) return SLAPO_ERR_NULL;
   if (N % 8 || misaligned(a) || misaligned(partials)) return SLAPO_ERR_ALIGN;
+  entry_error();
   launch_colsum_partials(dtype, T, N, a, partials, (hipStream_t)stream);
   return finish();
 }
@@ -719,6 +770,7 @@ int slapo_colreduce_partials(int dtype, int64_t nblk, int64_t stride, int64_t N,
   if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (nblk <= 0 || N <= 0 || stride < N) return SLAPO_ERR_SHAPE;
   if (!partials || !out) return SLAPO_ERR_NULL;
+  entry_error();
   launch_colreduce_partials(dtype, nblk, stride, N, partials, out, accumulate, (hipStream_t)stream);
   return finish();
 }
@@ -729,6 +781,7 @@ int slapo_dropout_mask(const slapo_layer_desc* d, int site, int64_t T, uint8_t* 
   if (T <= 0 || site < 0 || site > 1) return SLAPO_ERR_SHAPE;
   if (!mask) return SLAPO_ERR_NULL;
   if ((reinterpret_cast<uintptr_t>(mask) & 7u) != 0) return SLAPO_ERR_ALIGN;
+  entry_error();
   launch_dropout_mask(T * d->hidden, mask, make_dropout(d, site), (hipStream_t)stream);
   return finish();
 }

@@ -800,7 +800,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(int64_t chunks, int6
 // (measured: at M = N = 1024 four ranges take 41 us against 70 us at K = 16384, but 22.5 against 20.4 at K = 4096,
 // where the second kernel and the partial tiles cost more than the idle CUs).
 static int weight_grad_splits(int M, int N, int K) {
-  static const bool disabled = getenv("SLAPO_NO_SPLITK") && atoi(getenv("SLAPO_NO_SPLITK")) != 0;   // A/B timing
+  static const bool disabled = debug_flag("no-splitk");   // A/B timing
   if (disabled || K % 256 != 0 || N % 8 != 0) return 1;
   const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
   if (t128 >= 160) return 1;

@@ -6,6 +6,9 @@
 
 namespace slapo {
 
+// true if `name` is listed in the SLAPO_DEBUG environment variable (comma-separated debugging / A-B switches)
+bool debug_flag(const char* name);
+
 enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
 // EPI_GATE: the product's columns are (gate, up) pairs; C [M,N/2] = silu(gate) * up, aux_out [M,N] = the pair
 //   (up * silu'(gate), silu(gate)), the two factors backward multiplies the gradient of C with.

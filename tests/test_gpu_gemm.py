@@ -2,23 +2,17 @@
 import numpy as np
 import pytest
 import torch
-from scipy.special import erf
 
 import workloads as W
+from oracle import layer as L
 from paper_2302_08005_amd import binding as B
 from gpu_util import DEV, TOL, err, store, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
 
-def _act(u, act):
-    return 0.5 * u * (1 + erf(u / np.sqrt(2))) if act == W.GELU else np.maximum(u, 0)
-
-
-def _dact(u, act):
-    if act == W.RELU:
-        return (u > 0).astype(np.float64)
-    return 0.5 * (1 + erf(u / np.sqrt(2))) + u * np.exp(-0.5 * u * u) / np.sqrt(2 * np.pi)
+# the activation and its derivative are the oracle's own (pinned in tests/test_oracle_layer.py), not a second copy
+_act, _dact = L._act, L._act_grad
 
 
 # the last three reach the direct-load kernels with ragged edge tiles: 128x128 tiles fed by loader wavefronts

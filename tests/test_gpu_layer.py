@@ -56,6 +56,14 @@ def teacher_force(layer, cfg, ref):
         dst.copy_(src.to(dst.dtype))
 
 
+def saved_tol(cfg):
+    """Bar for the saved intermediates. They are sums over `hidden` (or ffn) products of operands that were
+    rounded to the storage type, so their rounding noise grows with the square root of the contraction length;
+    up to hidden 4096 (every benchmark shape is narrower) the stated bar is used as it is, beyond it the bar is
+    scaled by sqrt(hidden / 4096). Outputs and gradients are held to the stated bar at every width."""
+    return TOL[cfg.dtype] * max(1.0, (cfg.hidden / 4096.0) ** 0.5)
+
+
 def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True, teacher_forced_bwd=False):
     params = W.make_params(cfg, perturbed=perturbed)
     x, dy, sl = W.make_inputs(cfg, q_scale=q_scale)
@@ -66,7 +74,13 @@ def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True, teacher_forced_
     sld = None if sl is None else torch.from_numpy(sl).to(DEV)
     y = layer.forward(xd, sld)
     if teacher_forced_bwd:
+        # first the backward as it runs end to end, on the layer's own forward values: reported, not gated
+        dx_e2e = layer.backward(xd, sld, dyd)
         torch.cuda.synchronize()
+        e2e = {"dx": err(dx_e2e, gref["dx"])}
+        e2e.update({"d" + k: err(layer.grads[k], gref[k]) for k in W.PARAM_NAMES})
+        print(f"{cfg.name}: end-to-end backward (gate decisions taken from the GPU's own forward), not gated: "
+              + ", ".join(f"{k} {v:.2e}" for k, v in e2e.items()), flush=True)
         saved_errs = {"saved." + k: err(layer.saved_tensor(k).reshape(-1), ref[rk].reshape(-1))
                       for k, rk in (("g", "G"), ("z1", "Z1"), ("qkv", "QKV"), ("attn", "A"))}
         teacher_force(layer, cfg, ref)
@@ -76,6 +90,7 @@ def run_case(cfg, perturbed=True, q_scale=1.0, check_saved=True, teacher_forced_
     for k in W.PARAM_NAMES:
         errs["d" + k] = err(layer.grads[k], gref[k])
     if teacher_forced_bwd:
+        print(f"{cfg.name}: teacher-forced backward: " + ", ".join(f"{k} {v:.2e}" for k, v in errs.items() if k != "y"), flush=True)
         errs.update(saved_errs)
     if check_saved:
         ref = dict(ref, DACT=L._act_grad(ref["U"], cfg.act))
@@ -109,6 +124,53 @@ def test_layer_is_deterministic_and_accumulates():
     layer.backward(xd, sld, dyd)
     for k in W.PARAM_NAMES:
         assert err(layer.grads[k], 2 * to_np(g1[k])) <= 1e-2, k
+
+
+def test_backward_from_two_host_threads_on_one_device():
+    """Two host threads, each with its own layer, buffers and stream, run forward + backward at the same time.
+
+    Backward forks its weight gradients onto the device's one helper stream with events that the threads
+    share; every record and the wait that consumes it are issued under a lock, so each call waits for its own
+    records. The results must be the bits of the same calls made one after the other.
+    """
+    import threading
+    cfgs = [SMALL[4], SMALL[5]]
+    work = []
+    for cfg in cfgs:
+        params = W.make_params(cfg, perturbed=True)
+        x, dy, sl = W.make_inputs(cfg)
+        layer = B.Layer(cfg, params)
+        xd, dyd = layer.to_device(x), layer.to_device(dy)
+        sld = None if sl is None else torch.from_numpy(sl).to(DEV)
+        y = layer.forward(xd, sld)
+        dx = layer.backward(xd, sld, dyd)
+        torch.cuda.synchronize()
+        ref = (y.clone(), dx.clone(), {k: v.clone() for k, v in layer.grads.items()})
+        work.append((layer, xd, sld, dyd, ref))
+    failures = []
+
+    def run(i):
+        layer, xd, sld, dyd, (y0, dx0, g0) = work[i]
+        stream = torch.cuda.Stream(device=DEV)
+        with torch.cuda.stream(stream):
+            for it in range(40):
+                for g in layer.grads.values():
+                    g.zero_()
+                y = layer.forward(xd, sld)
+                dx = layer.backward(xd, sld, dyd)
+                stream.synchronize()
+                ok = torch.equal(y, y0) and torch.equal(dx, dx0) and all(torch.equal(layer.grads[k], g0[k]) for k in g0)
+                if not ok:
+                    failures.append((i, it))
+                    return
+
+    threads = [threading.Thread(target=run, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not failures, failures
 
 
 def test_zero_dropout_matches_layer_without_dropout_bitwise():
@@ -145,8 +207,10 @@ def test_layer_parity_full_size(key):
     cfg = W.CONFIGS[key[:2]]
     if key.endswith("-fp16"):
         cfg = cfg.replace(name=key, dtype=W.FP16)
-    # forward end to end; backward end to end too, except for bf16 ReLU layers (see teacher_force)
-    errs, _, _ = run_case(cfg, perturbed=False, check_saved=False, teacher_forced_bwd=(cfg.act == W.RELU))
+    # forward end to end; backward end to end too, except for bf16 ReLU layers (see teacher_force), whose
+    # end-to-end backward error is printed beside the teacher-forced one. C2 runs with the initialisation the
+    # benchmark states (biases 0, gains 1); the others with biases and gains drawn off their neutral values.
+    errs, _, _ = run_case(cfg, perturbed=(key != "C2"), check_saved=False, teacher_forced_bwd=(cfg.act == W.RELU))
     tol = TOL[cfg.dtype]
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, (bad, errs)
@@ -171,12 +235,11 @@ DEGENERATE = [
 
 @pytest.mark.parametrize("cfg", DEGENERATE, ids=lambda c: c.name)
 def test_layer_parity_degenerate_sizes(cfg):
-    # Outputs and all gradients are held to the tolerance at every width. The saved intermediates are compared
-    # up to hidden 4096 only: the FFN pre-activation is a sum over `hidden` products of bf16-rounded operands,
-    # its rounding noise grows with the square root of that length, and at 8192 the steepest part of GeLU'
-    # carries it just past 2e-2 on single elements of the saved derivative (2.2e-2 measured) while every
-    # gradient that is computed from it stays below 1e-2.
-    errs, _, _ = run_case(cfg, check_saved=cfg.hidden <= 4096)
-    tol = TOL[cfg.dtype]
-    bad = {k: v for k, v in errs.items() if not v <= tol}
+    # Outputs and all gradients are held to the stated tolerance at every width; the saved intermediates to
+    # saved_tol (the stated bar up to hidden 4096, scaled by sqrt(hidden / 4096) beyond: at 8192 the steepest
+    # part of GeLU' carries the sqrt(K) rounding noise of the FFN pre-activation to 2.2e-2 on single elements of
+    # the saved derivative, against a bar of 2.8e-2, while every gradient computed from it stays below 1e-2).
+    errs, _, _ = run_case(cfg)
+    tol, stol = TOL[cfg.dtype], saved_tol(cfg)
+    bad = {k: v for k, v in errs.items() if not v <= (stol if k.startswith("saved.") else tol)}
     assert not bad, (bad, errs)
