@@ -21,7 +21,7 @@
  *     slapo_layer_bwd issues its weight-gradient GEMMs on one internal helper stream per device, created
  *     on first use and kept for the life of the process, forked from and joined back into `stream` with
  *     events (capturable in a HIP graph like any fork/join). This helper stream and its events are the only
- *     state the library holds.
+ *     state the library holds besides the fixed scratch array of slapo_weight_grad_static.
  *   - Threads: every entry point may be called from several host threads at once, also on one device; calls
  *     touch only their own arguments. Backward calls of different threads on the same device share that
  *     device's helper stream: each event record and the stream wait that consumes it are issued under a
@@ -209,6 +209,20 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
 int slapo_weight_grad_workspace(int dtype, int64_t M, int64_t N, int64_t K, size_t *ws_bytes);
 int slapo_weight_grad(int dtype, int accumulate, int64_t M, int64_t N, int64_t K, const void *A, const void *B,
                       void *C, void *ws, void *stream);
+
+/* slapo_weight_grad for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving / training loops, harnesses that forbid allocation. Same arguments without `ws`, same
+ * results bit for bit. The fp32 partial tiles of the K-range path live in a fixed 16 MiB array in device memory that
+ * is part of the library's code object (one copy per GPU the library runs on, held until the process ends); the call
+ * allocates and frees nothing. A shape whose partial tiles would not fit returns SLAPO_ERR_WORKSPACE before anything
+ * is launched (with the current rule - at most 256 partial tiles of 128x128 - every shape fits; the check guards the
+ * array). The array keeps the last call's contents and nothing in it needs clearing: every partial tile a call reads
+ * it has written itself. All calls on one GPU share the array, so two calls whose work may overlap in time on one GPU
+ * (different streams, different host threads) race on it: order them, or use slapo_weight_grad with a workspace each.
+ * The device address of the array is looked up on the first call on each device; make that call outside any graph
+ * capture. At most 16 devices per process. */
+int slapo_weight_grad_static(int dtype, int accumulate, int64_t M, int64_t N, int64_t K, const void *A, const void *B,
+                             void *C, void *stream);
 
 /* Fused softmax attention over the packed projection qkv [B,S,3H] (Q | K | V on the last axis,
  * head a owning columns a*d..a*d+d-1 of each): out [B,S,H], lse [B,heads,S] fp32 holding

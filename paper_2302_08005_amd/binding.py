@@ -71,6 +71,7 @@ def lib():
             "slapo_rope": [dp, vp, vp, i32, vp],
             "slapo_weight_grad_workspace": [i32, i64, i64, i64, C.POINTER(C.c_size_t)],
             "slapo_weight_grad": [i32, i32, i64, i64, i64, vp, vp, vp, vp, vp],
+            "slapo_weight_grad_static": [i32, i32, i64, i64, i64, vp, vp, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -163,6 +164,11 @@ def slapo_weight_grad_workspace(dtype, M, N, K) -> int:
 def slapo_weight_grad(dtype, accumulate, M, N, K, A, B, Cout, ws=None, stream=None):
     _check(lib().slapo_weight_grad(dtype, accumulate, M, N, K, _p(A), _p(B), _p(Cout), _p(ws), _stream(stream)),
            "slapo_weight_grad")
+
+
+def slapo_weight_grad_static(dtype, accumulate, M, N, K, A, B, Cout, stream=None):
+    _check(lib().slapo_weight_grad_static(dtype, accumulate, M, N, K, _p(A), _p(B), _p(Cout), _stream(stream)),
+           "slapo_weight_grad_static")
 
 
 def slapo_attn_fwd(desc, qkv, seqlens, out, lse, stream=None):

@@ -678,6 +678,59 @@ int slapo_weight_grad(int dtype, int accumulate, int64_t M, int64_t N, int64_t K
   return finish();
 }
 
+// ---- the weight gradient for callers that cannot allocate ---------------------------------------------
+// Same computation as slapo_weight_grad, with the fp32 partial tiles of the K-range path in a fixed array in
+// device memory that belongs to the library instead of a caller-provided workspace. The array's name is only a
+// host-side handle: its device address is looked up once per device (with that device current) and kept, and
+// that pointer is what the kernels are given.
+}  // extern "C"
+
+namespace {
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[STATIC_SCRATCH_BYTES];
+
+// device address of this device's copy of g_static_scratch, or nullptr (with *status set) if it cannot be had
+float* static_scratch(int* status) {
+  static void* table[16] = {};
+  static std::mutex mu;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { *status = SLAPO_ERR_HIP; return nullptr; }
+  if (dev < 0 || dev >= 16) { *status = SLAPO_ERR_UNSUPPORTED; return nullptr; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!table[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      *status = SLAPO_ERR_HIP;
+      return nullptr;
+    }
+    table[dev] = ptr;
+  }
+  return (float*)table[dev];
+}
+}  // namespace
+
+extern "C" {
+
+int slapo_weight_grad_static(int dtype, int accumulate, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
+                             void* C, void* stream) {
+  const int rc = check_weight_grad_shape(dtype, M, N, K);
+  if (rc) return rc;
+  if (!A || !B || !C) return SLAPO_ERR_NULL;
+  if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
+  const size_t need = weight_grad_ws_bytes(dtype, (int)M, (int)N, (int)K);
+  if (need > STATIC_SCRATCH_BYTES) return SLAPO_ERR_WORKSPACE;
+  float* ws = nullptr;
+  if (need) {   // shapes that run as one plain GEMM touch no scratch at all
+    int st = SLAPO_OK;
+    ws = static_scratch(&st);
+    if (!ws) return st;
+  }
+  entry_error();
+  launch_weight_grad(dtype, accumulate ? 1 : 0, (int)M, (int)N, (int)K, A, B, C, ws, (hipStream_t)stream);
+  return finish();
+}
+
 int slapo_attn_fwd(const slapo_layer_desc* d, const void* qkv, const int32_t* seqlens, void* out, float* lse,
                    void* stream) {
   const int rc = check_desc(d);

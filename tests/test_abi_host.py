@@ -163,3 +163,21 @@ def test_weight_gradient_workspace_rule():
     assert lib.slapo_weight_grad(0, 0, 1024, 1024, 16384, 4096, 4096, 4096, None, None) == -1   # wants a workspace
     assert lib.slapo_weight_grad(0, 0, 1024, 1028, 16384, 4096, 4096, 4096, 4096, None) == -4
     assert lib.slapo_weight_grad(0, 0, 0, 1024, 4096, 4096, 4096, 4096, 4096, None) == -2
+
+
+def test_static_scratch_bound_and_argument_checks():
+    """slapo_weight_grad_static keeps its partial tiles in a fixed 16 MiB array: the K-range rule never asks for more
+    (at most 256 partial tiles of 128 x 128 floats), and its argument checks come before any device work."""
+    lib = B.lib()
+    worst = 0
+    for M in (8, 136, 1024, 1536, 2048, 2560, 4096, 12288):
+        for N in (8, 264, 1024, 1280, 2560, 4096):
+            for K in (256, 4096, 8192, 16384, 65536):
+                if M * K < 2 ** 31 and N * K < 2 ** 31:
+                    worst = max(worst, B.slapo_weight_grad_workspace(B.BF16, M, N, K))
+    assert 0 < worst <= 16 << 20
+    assert lib.slapo_weight_grad_static(0, 0, 1024, 1024, 16384, None, 4096, 4096, None) == -1
+    assert lib.slapo_weight_grad_static(0, 0, 1024, 1024, 16384, 4096 + 2, 4096, 4096, None) == -4
+    assert lib.slapo_weight_grad_static(0, 0, 1024, 1020, 16384, 4096, 4096, 4096, None) == -4
+    assert lib.slapo_weight_grad_static(0, 0, 0, 1024, 16384, 4096, 4096, 4096, None) == -2
+    assert lib.slapo_weight_grad_static(9, 0, 1024, 1024, 16384, 4096, 4096, 4096, None) == -3
