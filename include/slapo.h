@@ -200,6 +200,18 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
                const void *A, const void *B, void *C, const void *bias, const void *aux_in,
                void *aux_out, void *stream);
 
+/* slapo_gemm with the tile selection slapo_layer_bwd uses for the GEMMs of its data-gradient chain while the helper
+ * stream's weight gradients share the chip (slapo_gemm itself, like the forward pass, selects for a GEMM that runs
+ * alone: it may take 128x128 tiles where a grid of 256x256 tiles would end in a thin last round). For measurement. */
+int slapo_gemm_shared(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K,
+                      const void *A, const void *B, void *C, const void *bias, const void *aux_in,
+                      void *aux_out, void *stream);
+/* Writes the kernel instance a GEMM of this shape is launched as into buf (NUL-terminated, truncated to len), spelt
+ * as a profiler prints the symbol. shared != 0: the selection of slapo_gemm_shared; weight_grad != 0 (layout 2 only):
+ * the selection of slapo_weight_grad, K ranges included. Host-only. */
+int slapo_gemm_kernel_name(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, int shared,
+                           int weight_grad, char *buf, size_t len);
+
 /* Weight gradient C[M,N] (+)= A[K,M]^T B[K,N] (layout 2 with K = tokens; accumulate != 0 adds to C). When the
  * output has too few 128x128 tiles to fill the chip and K is a long multiple of 256 (at least 6144), the product is
  * computed in up to 8 K ranges at once, as fp32 partial tiles in `ws` that a second kernel adds in range order (bitwise

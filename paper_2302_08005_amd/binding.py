@@ -59,6 +59,8 @@ def lib():
             "slapo_stack_fwd": [dp, i32, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, vp, vp],
             "slapo_stack_bwd": [dp, i32, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, vp, C.POINTER(_Ptrs), vp, vp],
             "slapo_gemm": [i32, i32, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp],
+            "slapo_gemm_shared": [i32, i32, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp],
+            "slapo_gemm_kernel_name": [i32, i32, i32, i64, i64, i64, i32, i32, C.c_char_p, C.c_size_t],
             "slapo_attn_fwd": [dp, vp, vp, vp, vp, vp],
             "slapo_attn_bwd": [dp, vp, vp, vp, vp, vp, vp, vp, vp],
             "slapo_bdrln_fwd": [dp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
@@ -153,6 +155,18 @@ def slapo_layer_bwd(desc, params: dict, x, seqlens, dy, saved, dx, grads: dict, 
 def slapo_gemm(dtype, layout, epilogue, act, M, N, K, A, B, Cout, bias=None, aux_in=None, aux_out=None, stream=None):
     _check(lib().slapo_gemm(dtype, layout, epilogue, act, M, N, K, _p(A), _p(B), _p(Cout), _p(bias), _p(aux_in),
                             _p(aux_out), _stream(stream)), "slapo_gemm")
+
+
+def slapo_gemm_shared(dtype, layout, epilogue, act, M, N, K, A, B, Cout, bias=None, aux_in=None, aux_out=None, stream=None):
+    _check(lib().slapo_gemm_shared(dtype, layout, epilogue, act, M, N, K, _p(A), _p(B), _p(Cout), _p(bias), _p(aux_in),
+                                   _p(aux_out), _stream(stream)), "slapo_gemm_shared")
+
+
+def slapo_gemm_kernel_name(dtype, layout, epilogue, M, N, K, shared=0, weight_grad=0) -> str:
+    buf = C.create_string_buffer(256)
+    _check(lib().slapo_gemm_kernel_name(dtype, layout, epilogue, M, N, K, shared, weight_grad, buf, len(buf)),
+           "slapo_gemm_kernel_name")
+    return buf.value.decode()
 
 
 def slapo_weight_grad_workspace(dtype, M, N, K) -> int:

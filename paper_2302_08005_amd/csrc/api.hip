@@ -628,8 +628,8 @@ int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
   return SLAPO_OK;
 }
 
-int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
-               const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
+static int gemm_entry(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
+                      const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream, bool solo) {
   if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_DGATE) return SLAPO_ERR_UNSUPPORTED;
   if (act != SLAPO_GELU_ERF && act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
@@ -646,8 +646,29 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
   if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
   entry_error();
   launch_gemm(dtype, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
-              (hipStream_t)stream, true);
+              (hipStream_t)stream, solo);
   return finish();
+}
+
+int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
+               const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
+  return gemm_entry(dtype, layout, epilogue, act, M, N, K, A, B, C, bias, aux_in, aux_out, stream, true);
+}
+
+int slapo_gemm_shared(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
+                      const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
+  return gemm_entry(dtype, layout, epilogue, act, M, N, K, A, B, C, bias, aux_in, aux_out, stream, false);
+}
+
+int slapo_gemm_kernel_name(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, int shared,
+                           int weight_grad, char* buf, size_t len) {
+  if (!buf || len == 0) return SLAPO_ERR_NULL;
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
+  if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_DGATE) return SLAPO_ERR_UNSUPPORTED;
+  if (M <= 0 || N <= 0 || K <= 0 || M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31)) return SLAPO_ERR_SHAPE;
+  if (weight_grad && layout != GEMM_TN) return SLAPO_ERR_UNSUPPORTED;
+  describe_gemm(dtype, layout, epilogue, (int)M, (int)N, (int)K, !shared, weight_grad != 0, buf, len);
+  return SLAPO_OK;
 }
 
 static int check_weight_grad_shape(int dtype, int64_t M, int64_t N, int64_t K) {

@@ -9,6 +9,7 @@
 // strided one (the "N" operand of dY*W and both operands of dY^T*X) stay in their memory order in LDS and
 // are read with the transposing ds_read_b64_tr_b16, so no transposed copy of any tensor is ever made.
 // fp32 path: a plain LDS-tiled FMA kernel (correctness mode).
+#include <stdio.h>
 #include <stdlib.h>
 #include <type_traits>
 
@@ -734,9 +735,8 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
 // tiles: long K the same direct scheme with four computing wavefronts, else 128-deep slabs and two wave
 // sets splitting each slab. Other K go to the general kernel (one slab of register prefetch, zero-filled
 // tail).
-template <int LAYOUT, bool F16>
-static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
-                        const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo) {
+enum TileKind { TILE_256, TILE_128_SPLITSLAB, TILE_128_LOADERS, TILE_128_REGS, TILE_128x64_LOADERS, TILE_128x64_DEEP, TILE_GENERAL };
+static TileKind select_tile(int layout, int M, int N, int K, bool solo) {
   const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
   // A grid of 256x256 tiles runs in rounds of 256 (one workgroup per CU) and a thin last round costs a full one:
@@ -748,27 +748,40 @@ static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, co
   // 4.99 ms; on a single stream 5.06 against 5.62), so it is not applied there.
   bool big = K % 128 == 0 && t256 >= 192;
   if (solo && big && K % 256 == 0 && K >= 2048) {
-    const double e256 = LAYOUT == GEMM_NT ? 1.30 : LAYOUT == GEMM_NN ? 1.17 : 1.10, e128 = LAYOUT == GEMM_NT ? 1.05 : 1.0;
+    const double e256 = layout == GEMM_NT ? 1.30 : layout == GEMM_NN ? 1.17 : 1.10, e128 = layout == GEMM_NT ? 1.05 : 1.0;
     const double c256 = (double)((t256 + 255) / 256) * 4.0 / e256, c128 = (double)((t128 + 255) / 256) / e128;
     big = c256 <= c128;
   }
-  if (big)
-    launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (K % 256 == 0 && t128 >= 160 && LAYOUT == GEMM_TN)
-    // both operands go through the transposing LDS reads (two per fragment): the 64x64 wave tile of the
-    // split-slab form needs a third fewer of them per MFMA, worth 5-7 % on the weight-gradient shapes; the
-    // K-contiguous layouts gain nothing from it
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (K % 256 == 0 && t128 >= 160)
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (K % 128 == 0 && (t128 >= 160 || K % 256 != 0))
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 0, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (K % 256 == 0 && K >= 1024)
-    launch_bf16_tile<LAYOUT, 128, 64, 64, 2, 2, 1, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else if (K % 256 == 0)
-    launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, 0, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
-  else
-    launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+  if (big) return TILE_256;
+  // TN: both operands go through the transposing LDS reads (two per fragment): the 64x64 wave tile of the
+  // split-slab form needs a third fewer of them per MFMA, worth 5-7 % on the weight-gradient shapes; the
+  // K-contiguous layouts gain nothing from it
+  if (K % 256 == 0 && t128 >= 160) return layout == GEMM_TN ? TILE_128_SPLITSLAB : TILE_128_LOADERS;
+  if (K % 128 == 0 && (t128 >= 160 || K % 256 != 0)) return TILE_128_REGS;
+  if (K % 256 == 0 && K >= 1024) return TILE_128x64_LOADERS;
+  if (K % 256 == 0) return TILE_128x64_DEEP;
+  return TILE_GENERAL;
+}
+
+template <int LAYOUT, bool F16>
+static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
+                        const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo) {
+  switch (select_tile(LAYOUT, M, N, K, solo)) {
+    case TILE_256:
+      launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+    case TILE_128_SPLITSLAB:
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+    case TILE_128_LOADERS:
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+    case TILE_128_REGS:
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 4, 1, 2, 0, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+    case TILE_128x64_LOADERS:
+      launch_bf16_tile<LAYOUT, 128, 64, 64, 2, 2, 1, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+    case TILE_128x64_DEEP:
+      launch_bf16_tile<LAYOUT, 128, 64, 128, 2, 2, 2, 2, 0, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+    default:
+      launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+  }
 }
 
 // ---- weight gradients with few output tiles: several K ranges per tile ---------------------------------
@@ -843,6 +856,29 @@ void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const vo
   }
   if (dtype == DT_FP16) launch_splitk<true>(splits, accumulate, M, N, K, A, B, C, ws, st);
   else launch_splitk<false>(splits, accumulate, M, N, K, A, B, C, ws, st);
+}
+
+// The kernel instance a GEMM of this shape runs as, in the spelling of the kernel's template arguments
+// (layout, BM, BN, BK, WGM, WGN, KS, PF, NS, PW, KTAIL, epilogue, F16), as the profiler prints the symbol; for
+// the weight-gradient path (`weight_grad`) with its K ranges, if any.
+void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool solo, bool weight_grad, char* buf, size_t len) {
+  if (dtype == DT_FP32) { snprintf(buf, len, "gemm_f32_kernel<%d>", layout); return; }
+  const int f16 = dtype == DT_FP16 ? 1 : 0;
+  const char* b = f16 ? "true" : "false";
+  if (weight_grad) {
+    const int splits = weight_grad_splits(M, N, K);
+    if (splits > 1) {
+      snprintf(buf, len, "gemm_bf16_kernel<2, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, %d, %s> in %d K ranges + splitk_reduce_kernel", EPI_SPLITK, b, splits);
+      return;
+    }
+  }
+  static const char* const shape[] = {"256, 256, 64, 2, 4, 1, 2, 2, 0, false", "128, 128, 64, 2, 2, 2, 2, 4, 4, false",
+                                      "128, 128, 64, 2, 4, 1, 2, 4, 4, false", "128, 128, 64, 2, 4, 1, 2, 0, 0, false",
+                                      "128, 64, 64, 2, 2, 1, 2, 4, 4, false", "128, 64, 128, 2, 2, 2, 2, 0, 0, false",
+                                      "128, 128, 64, 2, 2, 1, 1, 0, 0, true"};
+  TileKind k = select_tile(layout, M, N, K, solo);
+  if (k != TILE_GENERAL && !epi_used(layout, epi)) k = TILE_GENERAL;   // epilogues the layer never pairs with this layout
+  snprintf(buf, len, "gemm_bf16_kernel<%d, %s, %d, %s>", layout, shape[(int)k], epi, b);
 }
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,

@@ -20,6 +20,7 @@ enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_ACT = 2, EPI_DACT = 3, EPI_ADD = 4, 
 // solo: nothing else runs beside this GEMM (it may then pick tiles by round count, see launch_bf16)
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
                  void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo = false);
+void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool solo, bool weight_grad, char* buf, size_t len);
 // Weight gradient C[M,N] (+)= A[K,M]^T B[K,N] (accumulate: add to C). Outputs with too few tiles to fill the
 // chip are computed in several K ranges at once (fp32 partial tiles in `ws`, summed in range order by a second
 // kernel: deterministic); weight_grad_ws_bytes says how much workspace a shape wants (0: none, plain GEMM).
