@@ -871,15 +871,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(AttnShape sh, con
       }
     }
   };
-  if (n_tiles > 0) {
-    issue_tile(0, 0);
-    __syncthreads();   // (waits for this wavefront's loads, then for everybody's)
-    for (int it = 0; it < n_tiles; ++it) {
-      if (it + 1 < n_tiles) issue_tile((it + 1) & 1, it + 1);   // that stage was last read before the barrier above
-      compute(it & 1, it);
-      __syncthreads();
-    }
-  }
+  tile_ring<2, 2 * TileDirect<D>::LEAST>(n_tiles, issue_tile, compute);
 
   if (my_q < S) {
     bf16_t* qrow = dqkv + ((int64_t)b * S + my_q) * rs + a * D;

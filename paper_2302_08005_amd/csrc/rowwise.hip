@@ -233,52 +233,68 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
   }
 }
 
-// The same backward for wide rows (H > 1024). The kernel above keeps a whole row and three column accumulators
-// per lane, which stops fitting the register file from H = 2048 on (it spills, and runs at a tenth of the
-// memory rate at H = 4096). Here the wavefronts of a block split the COLUMNS instead (thread c owns the 8
-// columns of chunk c, for every row the block visits) and walk the block's rows R at a time; the two per-row
-// sums cross the wavefronts through LDS, one barrier per R rows, added in wave order; the column sums never
-// leave their lane, so no reduction over wavefronts is needed at the end.
-template <typename T, bool LN, int R, int MAXW>
-__global__ __launch_bounds__(MAXW * 64) void bdrln_bwd_wide_kernel(
+// The same backward for rows of 512 elements and more. The kernel above keeps a whole row and three column
+// accumulators per lane, which stops fitting the register file from H = 2048 on, and it has one row per wavefront
+// in flight. Here a block is G groups of NW wavefronts; inside a group thread c owns the 8 columns of chunk c for
+// every row the group visits, so the column sums never leave their lane while the rows go by; the two per-row
+// sums cross the group's wavefronts through LDS (one barrier per step, added in wave order). A step handles R rows
+// per group, G * R consecutive rows per block, and the loads of the next step are issued before the arithmetic
+// of the current one (the barrier is a bare s_barrier: it does not wait for them), so that the block always has
+// two steps' worth of rows on their way from memory: with one block per CU (the partial sums it leaves are
+// [blocks, 3, H] floats, which bounds the block count) that is what keeps the memory pipeline full. At the end
+// the groups' column sums are added in group order through LDS: one partial row per block, as above.
+template <typename T, bool LN, int R, int MAXT>
+__global__ __launch_bounds__(MAXT) void bdrln_bwd_wide_kernel(
     int64_t rows, int H, const T* __restrict__ dout, const T* __restrict__ z, const float* __restrict__ mu,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres_in,
-    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp, int dr_from_stored) {
-  __shared__ float xs[2][R][MAXW][2];   // [parity][row][wave][s1, s2]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  const int c = threadIdx.x;
+    T* __restrict__ dz_out, T* __restrict__ dr_out, float* __restrict__ partials, DropoutParams dp, int dr_from_stored,
+    int NW, int G) {
+  extern __shared__ __attribute__((aligned(16))) float wsm[];   // per-row sums [2][G][R][NW][2]; at the end column sums [G-1][3][H]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int group = wave / NW, gw = wave - group * NW;
+  const int c = gw * 64 + lane;
   const bool active = c < (H >> 3);
   const float inv_h = 1.0f / (float)H;
   float pg[8], pb[8], pd[8], g[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { pg[e] = pb[e] = pd[e] = 0.f; g[e] = 0.f; }
   if (LN && active) load8(gamma + c * 8, g);
-  int par = 0;
-  for (int64_t row0 = (int64_t)blockIdx.x * R; row0 < rows; row0 += (int64_t)gridDim.x * R, par ^= 1) {
-    Raw8<T> rdy[R], rz[R], rres[R];
-    float m[R], rs[R];
-#pragma unroll
-    for (int j = 0; j < R; ++j) {   // all loads of the R rows go out before anything waits
-      const int64_t row = row0 + j;
-      m[j] = 0.f; rs[j] = 0.f;
-      if (row < rows) {
-        if (active) {
-          rdy[j].load(dout + row * H + c * 8);
-          if (LN) rz[j].load(z + row * H + c * 8);
-          if (dres_in) rres[j].load(dres_in + row * H + c * 8);
-        }
-        if (LN) { m[j] = mu ? mu[row] : 0.f; rs[j] = rstd[row]; }   // no mu: RMSNorm
-      }
-    }
-    float dy[R][8], xh[R][8], s1[R], s2[R];
+  const int64_t per_step = (int64_t)gridDim.x * G * R;
+  const int64_t n_steps = (rows + per_step - 1) / per_step;   // the same for every group: they share the barrier
+  auto first_row = [&](int64_t step) { return ((step * gridDim.x + blockIdx.x) * G + group) * R; };
+  Raw8<T> ndy[R], nz[R], nres[R];
+  float nm[R], nrs[R];
+  auto fetch = [&](int64_t step) {   // all loads of a step go out before anything waits
+    const int64_t row0 = first_row(step);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-      s1[j] = 0.f; s2[j] = 0.f;
+      const int64_t row = row0 + j;
+      nm[j] = 0.f; nrs[j] = 0.f;
+      if (row < rows) {
+        if (active) {
+          ndy[j].load(dout + row * H + c * 8);
+          if (LN) nz[j].load(z + row * H + c * 8);
+          if (dres_in) nres[j].load(dres_in + row * H + c * 8);
+        }
+        if (LN) { nm[j] = mu ? mu[row] : 0.f; nrs[j] = rstd[row]; }   // no mu: RMSNorm
+      }
+    }
+  };
+  if (n_steps > 0) fetch(0);
+  int par = 0;
+  for (int64_t step = 0; step < n_steps; ++step, par ^= 1) {
+    const int64_t row0 = first_row(step);
+    float dy[R][8], xh[R][8], s1[R], s2[R], m[R], rs[R];
+    Raw8<T> cres[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      s1[j] = 0.f; s2[j] = 0.f; m[j] = nm[j]; rs[j] = nrs[j];
       if (row0 + j < rows && active) {
-        rdy[j].get(dy[j]);
+        ndy[j].get(dy[j]);
+        if (dres_in) cres[j] = nres[j];
         if (LN) {
           float zz[8];
-          rz[j].get(zz);
+          nz[j].get(zz);
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             xh[j][e] = (zz[e] - m[j]) * rs[j];
@@ -291,17 +307,20 @@ __global__ __launch_bounds__(MAXW * 64) void bdrln_bwd_wide_kernel(
         }
       }
     }
+    if (step + 1 < n_steps) fetch(step + 1);   // on their way during the rest of this step
     if (LN) {
+      float* xs = wsm + (size_t)((par * G + group) * R) * NW * 2;
 #pragma unroll
       for (int j = 0; j < R; ++j) {
         const float a = wave_sum(s1[j]), b = wave_sum(s2[j]);
-        if (lane == 0) { xs[par][j][wave][0] = a; xs[par][j][wave][1] = b; }
+        if (lane == 0) { xs[(j * NW + gw) * 2] = a; xs[(j * NW + gw) * 2 + 1] = b; }
       }
-      __syncthreads();   // (the other parity is written next time round: no second barrier needed)
+      wait_loads_and_lds<63>();   // the LDS writes are done; the loads just issued stay in flight
+      block_barrier();            // (the other parity is written next time round: no second barrier needed)
 #pragma unroll
       for (int j = 0; j < R; ++j) {
         float a = 0.f, b = 0.f;
-        for (int w = 0; w < nw; ++w) { a += xs[par][j][w][0]; b += xs[par][j][w][1]; }
+        for (int w = 0; w < NW; ++w) { a += xs[(j * NW + w) * 2]; b += xs[(j * NW + w) * 2 + 1]; }
         s1[j] = mu ? a * inv_h : 0.f;
         s2[j] = b * inv_h;
       }
@@ -316,7 +335,7 @@ __global__ __launch_bounds__(MAXW * 64) void bdrln_bwd_wide_kernel(
         for (int e = 0; e < 8; ++e) dz[e] = LN ? rs[j] * (dy[j][e] - s1[j] - xh[j][e] * s2[j]) : dy[j][e];
         if (dres_in) {
           float res[8];
-          rres[j].get(res);
+          cres[j].get(res);
 #pragma unroll
           for (int e = 0; e < 8; ++e) dz[e] += res[e];
         }
@@ -335,7 +354,25 @@ __global__ __launch_bounds__(MAXW * 64) void bdrln_bwd_wide_kernel(
       }
     }
   }
-  if (active) {
+  // column sums of the groups, added in group order
+  __syncthreads();   // the per-row sums in LDS have been read by everybody
+  if (group > 0 && active) {
+    float* slot = wsm + (size_t)(group - 1) * 3 * H;
+    store8(slot + c * 8, pg);
+    store8(slot + H + c * 8, pb);
+    store8(slot + 2 * H + c * 8, pd);
+  }
+  __syncthreads();
+  if (group == 0 && active) {
+    for (int gg = 1; gg < G; ++gg) {
+      const float* slot = wsm + (size_t)(gg - 1) * 3 * H;
+      float a[8], b[8], d[8];
+      load8(slot + c * 8, a);
+      load8(slot + H + c * 8, b);
+      load8(slot + 2 * H + c * 8, d);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { pg[e] += a[e]; pb[e] += b[e]; pd[e] += d[e]; }
+    }
     float* prow = partials + (size_t)blockIdx.x * 3 * H;
     store8(prow + c * 8, pg);
     store8(prow + H + c * 8, pb);
@@ -474,17 +511,28 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
                        const void* gamma, const void* dres_in, void* dz_out, void* dr_out, float* partials,
                        const DropoutParams& dp, int dr_from_stored, hipStream_t st) {
   const int blocks = bdrln_bwd_blocks(rows);
-  if (H / 8 > 128) {   // wide rows: columns split over the wavefronts of a block (at most 8 of them up to H = 4096,
-                       // 16 up to 8192: a kernel of its own, because the larger block halves the register budget)
-    const int waves = (H / 8 + 63) / 64;
-    if (waves <= 8)
-      hipLaunchKernelGGL((bdrln_bwd_wide_kernel<T, LN, 4, 8>), dim3(blocks), dim3(waves * 64), 0, st, rows, H, (const T*)dout,
-                         (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,
-                         dr_from_stored);
-    else
-      hipLaunchKernelGGL((bdrln_bwd_wide_kernel<T, LN, 2, 16>), dim3(blocks), dim3(waves * 64), 0, st, rows, H, (const T*)dout,
-                         (const T*)z, mu, rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,
-                         dr_from_stored);
+  if (H >= 512) {
+    // Groups of NW wavefronts that split the columns. Up to hidden 3072 as many groups as fit 12 wavefronts (the
+    // register budget of three wavefronts per SIMD holds two rows per group and their prefetch without spilling);
+    // wider rows fill the block with one group, four rows at a time up to 4096, one above.
+    const int nw = (H / 8 + 63) / 64;
+    const int groups = nw <= 6 ? (12 / nw > 8 ? 8 : 12 / nw) : 1;
+    const int rows_per_group = nw <= 6 ? 2 : nw <= 8 ? 4 : 1;
+    const size_t xs_bytes = (size_t)2 * groups * rows_per_group * nw * 2 * sizeof(float);
+    const size_t col_bytes = (size_t)(groups - 1) * 3 * H * sizeof(float);
+    const size_t lds = xs_bytes > col_bytes ? xs_bytes : col_bytes;
+#define SLAPO_WIDE(R, MAXT)                                                                                          \
+  do {                                                                                                               \
+    auto kern = bdrln_bwd_wide_kernel<T, LN, R, MAXT>;                                                               \
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);             \
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(groups * nw * 64), lds, st, rows, H, (const T*)dout, (const T*)z, mu, \
+                       rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,              \
+                       dr_from_stored, nw, groups);                                                                  \
+  } while (0)
+    if (nw <= 6) SLAPO_WIDE(2, 768);
+    else if (nw <= 8) SLAPO_WIDE(4, 512);
+    else SLAPO_WIDE(1, 1024);
+#undef SLAPO_WIDE
     return;
   }
 #define SLAPO_BWD(N, W)                                                                                      \
