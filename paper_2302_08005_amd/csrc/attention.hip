@@ -82,6 +82,9 @@ __device__ __forceinline__ void mfma16_agpr(f32x16_t& acc, bf16x8_t a, bf16x8_t 
   if constexpr (F16) asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
   else asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
+// The value exists in ordinary registers at this point of the program: an ordering anchor for operations that
+// have no side effects of their own (nothing is emitted).
+__device__ __forceinline__ void pin_here(f32x16_t& v) { asm volatile("" : "+v"(v)); }
 // more wait states than any MFMA needs before its result may be read by a non-MFMA instruction
 __device__ __forceinline__ void agpr_results_ready() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 // row index inside a 32x32 accumulator tile of register r
@@ -505,11 +508,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
         f32x16_t sc0, dp0, sc1, dp1;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sc0[r] = dp0[r] = sc1[r] = dp1[r] = 0.f;
-        auto element = [&](f32x16_t& sc, f32x16_t& dp, int r, float ls, float ds) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -ls));
-          sc[r] = p;
-          dp[r] = p * (dp[r] - ds);
-        };
         // scores of sub-tile 0
 #pragma unroll
         for (int s0 = 0; s0 < NS; s0 += FB) {
@@ -527,37 +525,60 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        // scores of sub-tile 1 (two k-steps = four MFMAs per round) || softmax of sub-tile 0 (four elements per round)
+        // The 16 score elements of a sub-tile go through three steps each - a = sc * scale - lse; p = exp2(a);
+        // sc = p, dp = p * (dp - delta) - and run as a pipeline beside 16 MFMAs of the OTHER sub-tile: the slot of
+        // MFMA s holds step 1 of element s + 1, step 2 of element s and step 3 of element s - 1, so no vector
+        // instruction waits for the result of the one in front of it (one element's steps back to back are a
+        // dependent chain whose latencies nothing hides with a single wavefront per SIMD). The row statistics of
+        // four elements (one float4 each of lse and delta) are read from LDS three slots ahead of their first use.
+        auto pick = [](const float4& v, int e) { return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w; };
+        auto soft_slots = [&](f32x16_t& sc, f32x16_t& dp, const float* srow, auto&& mfma_slot) {
+          float4 l[2], d[2];
+          l[0] = *reinterpret_cast<const float4*>(srow + 4 * kc);
+          d[0] = *reinterpret_cast<const float4*>(srow + 64 + 4 * kc);
+          float a_next = fmaf(sc[0], sl2, -l[0].x), p_prev = 0.f;
+#pragma unroll
+          for (int s = 0; s < 16; ++s) {
+            const int g = s >> 2, e = s & 3;
+            if (e == 1 && g + 1 < 4) {
+              l[(g + 1) & 1] = *reinterpret_cast<const float4*>(srow + (g + 1) * 8 + 4 * kc);
+              d[(g + 1) & 1] = *reinterpret_cast<const float4*>(srow + 64 + (g + 1) * 8 + 4 * kc);
+            }
+            mfma_slot(s);
+            const float a_cur = a_next;
+            if (s + 1 < 16) a_next = fmaf(sc[s + 1], sl2, -pick(l[((s + 1) >> 2) & 1], (s + 1) & 3));
+            const float p_cur = __builtin_amdgcn_exp2f(a_cur);
+            if (s > 0) {
+              sc[s - 1] = p_prev;
+              dp[s - 1] = p_prev * (dp[s - 1] - pick(d[((s - 1) >> 2) & 1], (s - 1) & 3));
+            }
+            p_prev = p_cur;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          sc[15] = p_prev;
+          dp[15] = p_prev * (dp[15] - d[1].w);
+        };
+        // scores of sub-tile 1 (two k-steps = four MFMAs per round) || softmax of sub-tile 0
         {
           bf16x8_t fq[2][2], fd[2][2];
 #pragma unroll
           for (int k = 0; k < 2; ++k) { fq[0][k] = frag_rows<D>(qtile, fr_base, 32, k); fd[0][k] = frag_rows<D>(dtile, fr_base, 32, k); }
-#pragma unroll
-          for (int g = 0; g < NS / 2; ++g) {
-            const int cur = g & 1;
-            if (g + 1 < NS / 2) {
+          soft_slots(sc0, dp0, stats, [&](int s) {
+            const int g = s >> 2, e = s & 3, cur = g & 1;
+            if (e == 0 && g + 1 < NS / 2) {
 #pragma unroll
               for (int k = 0; k < 2; ++k) {
                 fq[cur ^ 1][k] = frag_rows<D>(qtile, fr_base, 32, 2 * g + 2 + k);
                 fd[cur ^ 1][k] = frag_rows<D>(dtile, fr_base, 32, 2 * g + 2 + k);
               }
             }
-            const float4 l4 = *reinterpret_cast<const float4*>(stats + g * 8 + 4 * kc);
-            const float4 d4 = *reinterpret_cast<const float4*>(stats + 64 + g * 8 + 4 * kc);
-            __builtin_amdgcn_sched_barrier(0);
-            sc1 = mfma16<F16>(fq[cur][0], kf[2 * g], sc1);
-            element(sc0, dp0, 4 * g + 0, l4.x, d4.x);
-            __builtin_amdgcn_sched_barrier(0);
-            dp1 = mfma16<F16>(fd[cur][0], vf[2 * g], dp1);
-            element(sc0, dp0, 4 * g + 1, l4.y, d4.y);
-            __builtin_amdgcn_sched_barrier(0);
-            sc1 = mfma16<F16>(fq[cur][1], kf[2 * g + 1], sc1);
-            element(sc0, dp0, 4 * g + 2, l4.z, d4.z);
-            __builtin_amdgcn_sched_barrier(0);
-            dp1 = mfma16<F16>(fd[cur][1], vf[2 * g + 1], dp1);
-            element(sc0, dp0, 4 * g + 3, l4.w, d4.w);
-            __builtin_amdgcn_sched_barrier(0);
-          }
+            // (a compiler-visible MFMA is a pure operation that the instruction selector may move past scheduling
+            // barriers - all sixteen ended up behind the softmax; the empty statement pins its result to this slot)
+            if (e == 0) { sc1 = mfma16<F16>(fq[cur][0], kf[2 * g], sc1); pin_here(sc1); }
+            else if (e == 1) { dp1 = mfma16<F16>(fd[cur][0], vf[2 * g], dp1); pin_here(dp1); }
+            else if (e == 2) { sc1 = mfma16<F16>(fq[cur][1], kf[2 * g + 1], sc1); pin_here(sc1); }
+            else { dp1 = mfma16<F16>(fd[cur][1], vf[2 * g + 1], dp1); pin_here(dp1); }
+          });
         }
         // dV, dK of sub-tile 0 (four MFMAs per round) || softmax of sub-tile 1
         {
@@ -565,10 +586,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
           bf16x8_t td[2][2], tq[2][2];   // [round parity][column block of the round]
 #pragma unroll
           for (int k = 0; k < 2; ++k) { td[0][k] = frag_tr<D>(dtile, ft_base, 0, k); tq[0][k] = frag_tr<D>(qtile, ft_base, 0, k); }
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {   // round g: half h = g / 2, column blocks t = 2 (g % 2), 2 (g % 2) + 1
-            const int cur = g & 1, h = g >> 1, t0 = 2 * (g & 1);
-            if (g + 1 < 4) {
+          soft_slots(sc1, dp1, stats + 32, [&](int s) {   // round g: half h = g / 2, column blocks t = 2 (g % 2), 2 (g % 2) + 1
+            const int g = s >> 2, e = s & 3, cur = g & 1, h = g >> 1, t0 = 2 * (g & 1);
+            if (e == 0 && g + 1 < 4) {
               const int hn = (g + 1) >> 1, tn = 2 * ((g + 1) & 1);
 #pragma unroll
               for (int k = 0; k < 2; ++k) {
@@ -576,22 +596,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_bf16_kernel(AttnShape sh, c
                 tq[cur ^ 1][k] = frag_tr<D>(qtile, ft_base, 16 * hn, tn + k);
               }
             }
-            const float4 l4 = *reinterpret_cast<const float4*>(stats + 32 + g * 8 + 4 * kc);
-            const float4 d4 = *reinterpret_cast<const float4*>(stats + 64 + 32 + g * 8 + 4 * kc);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma16_agpr<F16>(dv[t0], td[cur][0], pf[h]);
-            element(sc1, dp1, 4 * g + 0, l4.x, d4.x);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma16_agpr<F16>(dk[t0], tq[cur][0], dsf[h]);
-            element(sc1, dp1, 4 * g + 1, l4.y, d4.y);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma16_agpr<F16>(dv[t0 + 1], td[cur][1], pf[h]);
-            element(sc1, dp1, 4 * g + 2, l4.z, d4.z);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma16_agpr<F16>(dk[t0 + 1], tq[cur][1], dsf[h]);
-            element(sc1, dp1, 4 * g + 3, l4.w, d4.w);
-            __builtin_amdgcn_sched_barrier(0);
-          }
+            if (e == 0) mfma16_agpr<F16>(dv[t0], td[cur][0], pf[h]);
+            else if (e == 1) mfma16_agpr<F16>(dk[t0], tq[cur][0], dsf[h]);
+            else if (e == 2) mfma16_agpr<F16>(dv[t0 + 1], td[cur][1], pf[h]);
+            else mfma16_agpr<F16>(dk[t0 + 1], tq[cur][1], dsf[h]);
+          });
         }
         // dV, dK of sub-tile 1
         {
