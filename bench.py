@@ -178,16 +178,18 @@ def kernel_figures(B, cfg, layer, xd, dyd, sld, seqlens, reps, stream, verbose=F
     rows = []   # (name, algorithmic flop, fn, kernel instance)
 
     def gemm(name, shared, layout, epi, M, N, K, a, b, c, **kw):
-        f = B.slapo_gemm_shared if shared else B.slapo_gemm
-        rows.append((name, 2.0 * M * N * K, lambda: f(dt, layout, epi, act, M, N, K, a, b, c, **kw),
-                     B.slapo_gemm_kernel_name(dt, layout, epi, M, N, K, shared=int(shared))))
+        flags = B.GEMM_SHARED if shared else 0
+        nbytes = B.slapo_gemm_workspace(dt, layout, epi, M, N, K)   # (the layer hands its GEMMs a region of its scratch)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
+        rows.append((name, 2.0 * M * N * K, lambda: B.slapo_gemm_ex(dt, layout, epi, act, M, N, K, a, b, c, flags=flags, ws=ws, **kw),
+                     B.slapo_gemm_kernel_name(dt, layout, epi, M, N, K, flags=flags, with_ws=1)))
 
     def wgrad(name, M, N, K, a, b):
         nbytes = B.slapo_weight_grad_workspace(dt, M, N, K)
         ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
         c = torch.empty(M, N, device="cuda", dtype=tdt)
         rows.append((name, 2.0 * M * N * K, lambda: B.slapo_weight_grad(dt, 0, M, N, K, a, b, c, ws),
-                     B.slapo_gemm_kernel_name(dt, B.TN, B.EPI_NONE, M, N, K, shared=1, weight_grad=1)))
+                     B.slapo_gemm_kernel_name(dt, B.TN, B.EPI_NONE, M, N, K, flags=B.GEMM_SHARED, weight_grad=1, with_ws=1)))
 
     # forward: the GEMM has the chip to itself
     if llama:

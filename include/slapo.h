@@ -200,22 +200,33 @@ int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t 
                const void *A, const void *B, void *C, const void *bias, const void *aux_in,
                void *aux_out, void *stream);
 
-/* slapo_gemm with the tile selection slapo_layer_bwd uses for the GEMMs of its data-gradient chain while the helper
- * stream's weight gradients share the chip (slapo_gemm itself, like the forward pass, selects for a GEMM that runs
- * alone: it may take 128x128 tiles where a grid of 256x256 tiles would end in a thin last round). For measurement. */
-int slapo_gemm_shared(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K,
-                      const void *A, const void *B, void *C, const void *bias, const void *aux_in,
-                      void *aux_out, void *stream);
+/* slapo_gemm with options, as the layer calls use the kernels.
+ *   flags: SLAPO_GEMM_SHARED selects tiles as slapo_layer_bwd does for the GEMMs of its data-gradient chain while the
+ *          helper stream's weight gradients share the chip (slapo_gemm, like the forward pass, selects for a GEMM that
+ *          runs alone: it may take 128x128 tiles where a grid of 256x256 tiles would end in a thin last round).
+ *   ws, ws_bytes: optional device workspace (16-byte aligned; free again when the call's work is done). With it, a
+ *          plain or add-epilogue GEMM (epilogue 0 or 4) whose grid of 256x256 tiles is not a multiple of the 256 CUs
+ *          and whose K is long computes the tiles beyond the last full round in several K ranges (fp32 partial tiles
+ *          in ws, added in range order by a second kernel: bitwise reproducible), so that the last round is short
+ *          instead of thin. slapo_gemm_workspace writes the bytes a shape can use (0: it runs as slapo_gemm would);
+ *          a non-NULL ws smaller than that is refused with SLAPO_ERR_WORKSPACE. The layer calls do the same with a
+ *          region of their scratch buffer. */
+enum { SLAPO_GEMM_SHARED = 1 };
+int slapo_gemm_workspace(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, size_t *ws_bytes);
+int slapo_gemm_ex(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K,
+                  const void *A, const void *B, void *C, const void *bias, const void *aux_in,
+                  void *aux_out, int flags, void *ws, size_t ws_bytes, void *stream);
 /* Writes the kernel instance a GEMM of this shape is launched as into buf (NUL-terminated, truncated to len), spelt
- * as a profiler prints the symbol. shared != 0: the selection of slapo_gemm_shared; weight_grad != 0 (layout 2 only):
- * the selection of slapo_weight_grad, K ranges included. Host-only. */
-int slapo_gemm_kernel_name(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, int shared,
-                           int weight_grad, char *buf, size_t len);
+ * as a profiler prints the symbol. flags as for slapo_gemm_ex; with_ws != 0: as launched with a sufficient
+ * workspace; weight_grad != 0 (layout 2 only): the selection of slapo_weight_grad, K ranges included. Host-only. */
+int slapo_gemm_kernel_name(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, int flags,
+                           int weight_grad, int with_ws, char *buf, size_t len);
 
 /* Weight gradient C[M,N] (+)= A[K,M]^T B[K,N] (layout 2 with K = tokens; accumulate != 0 adds to C). When the
  * output has too few 128x128 tiles to fill the chip and K is a long multiple of 256 (at least 6144), the product is
  * computed in up to 8 K ranges at once, as fp32 partial tiles in `ws` that a second kernel adds in range order (bitwise
- * reproducible). slapo_weight_grad_workspace writes the bytes of `ws` a shape wants (0: the plain GEMM is used
+ * reproducible); an output with many tiles whose grid ends in a thin round uses `ws` as slapo_gemm_ex does.
+ * slapo_weight_grad_workspace writes the bytes of `ws` a shape wants (0: the plain GEMM is used
  * and ws may be NULL; also for SLAPO_FP32). ws: device, 16-byte aligned, free again when the call's work is done.
  * slapo_layer_bwd uses this path for its four weight gradients with a region of its scratch buffer. */
 int slapo_weight_grad_workspace(int dtype, int64_t M, int64_t N, int64_t K, size_t *ws_bytes);

@@ -59,8 +59,9 @@ def lib():
             "slapo_stack_fwd": [dp, i32, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, vp, vp],
             "slapo_stack_bwd": [dp, i32, C.POINTER(_Ptrs), vp, vp, vp, vp, vp, vp, C.POINTER(_Ptrs), vp, vp],
             "slapo_gemm": [i32, i32, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp],
-            "slapo_gemm_shared": [i32, i32, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp],
-            "slapo_gemm_kernel_name": [i32, i32, i32, i64, i64, i64, i32, i32, C.c_char_p, C.c_size_t],
+            "slapo_gemm_ex": [i32, i32, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32, vp, C.c_size_t, vp],
+            "slapo_gemm_workspace": [i32, i32, i32, i64, i64, i64, C.POINTER(C.c_size_t)],
+            "slapo_gemm_kernel_name": [i32, i32, i32, i64, i64, i64, i32, i32, i32, C.c_char_p, C.c_size_t],
             "slapo_attn_fwd": [dp, vp, vp, vp, vp, vp],
             "slapo_attn_bwd": [dp, vp, vp, vp, vp, vp, vp, vp, vp],
             "slapo_bdrln_fwd": [dp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp],
@@ -157,14 +158,25 @@ def slapo_gemm(dtype, layout, epilogue, act, M, N, K, A, B, Cout, bias=None, aux
                             _p(aux_out), _stream(stream)), "slapo_gemm")
 
 
-def slapo_gemm_shared(dtype, layout, epilogue, act, M, N, K, A, B, Cout, bias=None, aux_in=None, aux_out=None, stream=None):
-    _check(lib().slapo_gemm_shared(dtype, layout, epilogue, act, M, N, K, _p(A), _p(B), _p(Cout), _p(bias), _p(aux_in),
-                                   _p(aux_out), _stream(stream)), "slapo_gemm_shared")
+GEMM_SHARED = 1
 
 
-def slapo_gemm_kernel_name(dtype, layout, epilogue, M, N, K, shared=0, weight_grad=0) -> str:
-    buf = C.create_string_buffer(256)
-    _check(lib().slapo_gemm_kernel_name(dtype, layout, epilogue, M, N, K, shared, weight_grad, buf, len(buf)),
+def slapo_gemm_workspace(dtype, layout, epilogue, M, N, K) -> int:
+    a = C.c_size_t(0)
+    _check(lib().slapo_gemm_workspace(dtype, layout, epilogue, M, N, K, C.byref(a)), "slapo_gemm_workspace")
+    return a.value
+
+
+def slapo_gemm_ex(dtype, layout, epilogue, act, M, N, K, A, B, Cout, bias=None, aux_in=None, aux_out=None, flags=0, ws=None,
+                  stream=None):
+    _check(lib().slapo_gemm_ex(dtype, layout, epilogue, act, M, N, K, _p(A), _p(B), _p(Cout), _p(bias), _p(aux_in),
+                               _p(aux_out), flags, _p(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                               _stream(stream)), "slapo_gemm_ex")
+
+
+def slapo_gemm_kernel_name(dtype, layout, epilogue, M, N, K, flags=0, weight_grad=0, with_ws=0) -> str:
+    buf = C.create_string_buffer(320)
+    _check(lib().slapo_gemm_kernel_name(dtype, layout, epilogue, M, N, K, flags, weight_grad, with_ws, buf, len(buf)),
            "slapo_gemm_kernel_name")
     return buf.value.decode()
 

@@ -192,7 +192,7 @@ SavedLayout saved_layout(const slapo_layer_desc* d) {
 }
 
 struct ScratchLayout {
-  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, rope, splitk, acts, total;
+  size_t t0, t1, t2, t3, du, dqkv, delta, part_row, part_col, part_col2, rope, splitk, gemm_ws, gemm_ws_bytes, splitk_bytes, acts, total;
 };
 ScratchLayout scratch_layout(const slapo_layer_desc* d) {
   const size_t eb = d->dtype == SLAPO_FP32 ? 4 : 2;
@@ -221,6 +221,18 @@ ScratchLayout scratch_layout(const slapo_layer_desc* d) {
     const size_t wq = weight_grad_ws_bytes(d->dtype, 3 * Ai, Hi, Ti);
     w = w > w1 ? w : w1; w = w > wo ? w : wo; w = w > wq ? w : wq;
     L.splitk = w ? take(w) : 0;
+    L.splitk_bytes = w;
+    // the same kind of workspace for the GEMMs of the forward pass and of the data-gradient chain whose tile grid
+    // would end in a thin round (their last tiles are then computed in K ranges); a region of its own, because
+    // the chain runs while the helper stream's weight gradients use the one above
+    size_t g = gemm_ws_bytes(d->dtype, EPI_NONE, Ti, Hi, Ai);                       // attention output projection
+    auto upto = [&](size_t v) { g = g > v ? g : v; };
+    upto(gemm_ws_bytes(d->dtype, EPI_NONE, Ti, Hi, Fi));                             // second FFN product
+    upto(gemm_ws_bytes(d->dtype, EPI_NONE, Ti, Hi, F1));                             // gradient of the FFN input
+    upto(gemm_ws_bytes(d->dtype, EPI_NONE, Ti, Ai, Hi));                             // gradient of the attention output
+    upto(gemm_ws_bytes(d->dtype, EPI_NONE, Ti, Hi, 3 * Ai));                         // gradient of the attention input
+    L.gemm_ws = g ? take(g) : 0;
+    L.gemm_ws_bytes = g;
   }
   // checkpoint mode: the activations that forward would hand to backward live here instead, for the
   // duration of one call only (backward recomputes them), so the caller keeps nothing per layer but x
@@ -333,7 +345,8 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
     launch_gemm(dt, GEMM_NT, EPI_BIAS, d->act, T, 3 * A, H, attn_in, p->wqkv, qkv, p->bqkv, nullptr, nullptr, st, true);
   }
   launch_attn_fwd(dt, as, qkv, seqlens, attn, lse, st);
-  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, A, attn, p->wo, r, nullptr, nullptr, nullptr, st, true);
+  float* gws = W.gemm_ws_bytes ? (float*)(sc + W.gemm_ws) : nullptr;   // for GEMMs whose tile grid ends in a thin round
+  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, A, attn, p->wo, r, nullptr, nullptr, nullptr, st, true, gws, W.gemm_ws_bytes);
   const void* bo = llama ? nullptr : p->bo;
   const void* b2 = llama ? nullptr : p->b2;
   if (d->pre_ln) launch_bdrln_fwd(dt, T, H, r, bo, x, p->ln2_g, p->ln2_b, z1, y1, mu2, rstd2, dp0, d->ln_eps, rms, st);
@@ -345,7 +358,7 @@ static void run_forward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   // Backward of a pre-LN layer reads nothing downstream of the activation output (its last step has no
   // LayerNorm whose input would have to be kept), so a recomputation stops here: one GEMM in six less.
   if (for_backward && d->pre_ln) return;
-  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st, true);
+  launch_gemm(dt, GEMM_NT, EPI_NONE, d->act, T, H, F, g, p->w2, r, nullptr, nullptr, nullptr, st, true, gws, W.gemm_ws_bytes);
   if (d->pre_ln && link && link->above) {
     char* up = (char*)link->above_saved;
     launch_bdrln_fwd(dt, T, H, r, b2, z1, link->above->ln1_g, llama ? nullptr : link->above->ln1_b, y, up + L.n1,
@@ -437,7 +450,9 @@ static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, 
     if (side) side->order(side->fork[i], st, ws);
   };
   // weight gradient: C (+)= A^T B
-  float* splitk_ws = W.splitk ? (float*)(sc + W.splitk) : nullptr;
+  float* splitk_ws = W.splitk_bytes ? (float*)(sc + W.splitk) : nullptr;
+  float* gws = W.gemm_ws_bytes ? (float*)(sc + W.gemm_ws) : nullptr;
+  const size_t gwb = W.gemm_ws_bytes;
   auto dweight = [&](int M, int N, const void* a, const void* b, void* c) {
     launch_weight_grad(dt, acc, M, N, T, a, b, c, splitk_ws, ws, solo);
   };
@@ -475,14 +490,14 @@ static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, 
     launch_gemm(dt, GEMM_NN, EPI_DGATE, d->act, T, F, H, dr2, p->w2, du, nullptr, u, nullptr, st, solo);
     fork(1);
     dweight(2 * F, H, du, y1, gr->w1);
-    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 2 * F, du, p->w1, t0, nullptr, nullptr, nullptr, st, solo);
+    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 2 * F, du, p->w1, t0, nullptr, nullptr, nullptr, st, solo, gws, gwb);
   } else {
     launch_gemm(dt, GEMM_NN, EPI_DACT, d->act, T, F, H, dr2, p->w2, du, nullptr, u, nullptr, st, solo);
     fork(1);
     colsum(du, F, gr->b1, ws);
     dweight(F, H, du, y1, gr->w1);
-    if (d->pre_ln) launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st, solo);
-    else launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st, solo);
+    if (d->pre_ln) launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, F, du, p->w1, t0, nullptr, nullptr, nullptr, st, solo, gws, gwb);
+    else launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, F, du, p->w1, t0, nullptr, t0, nullptr, st, solo, gws, gwb);
   }
   // ---- attention block ----
   if (d->pre_ln) {
@@ -494,7 +509,7 @@ static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   }
   fork(2);
   dweight(H, A, t3, attn, gr->wo);
-  launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, A, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st, solo);
+  launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, A, H, t3, p->wo, t0, nullptr, nullptr, nullptr, st, solo, gws, gwb);
   launch_attn_bwd(dt, as, qkv, seqlens, attn, t0, lse, delta, dqkv, st);
   if (llama) {
     // the attention gradients are w.r.t. the rotated queries and keys: turn them back (the rotation's transpose)
@@ -505,7 +520,7 @@ static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, 
   fork(3);
   if (d->pre_ln) {
     dweight(3 * A, H, dqkv, sv + L.n1, gr->wqkv);
-    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * A, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st, solo);
+    launch_gemm(dt, GEMM_NN, EPI_NONE, d->act, T, H, 3 * A, dqkv, p->wqkv, t0, nullptr, nullptr, nullptr, st, solo, gws, gwb);
     if (link && link->dr2_below) {
       // (from the stored dx, so that the layer below sees what it would compute from dx itself, bit for bit)
       launch_bdrln_bwd(dt, T, H, t0, x, mu1, rstd1, p->ln1_g, t2, dx, link->dr2_below, prow, link->dp_below, rms, st, 1);
@@ -516,7 +531,7 @@ static int run_backward(const slapo_layer_desc* d, const slapo_layer_params* p, 
     }
   } else {
     dweight(3 * A, H, dqkv, x, gr->wqkv);
-    launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * A, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st, solo);
+    launch_gemm(dt, GEMM_NN, EPI_ADD, d->act, T, H, 3 * A, dqkv, p->wqkv, dx, nullptr, t2, nullptr, st, solo, gws, gwb);
   }
   // the last bias gradient goes behind the data gradient on the caller's stream: the helper stream's last
   // product is the longer one, and this way the two streams end at about the same time
@@ -629,7 +644,8 @@ int slapo_stack_bwd(const slapo_layer_desc* desc, int32_t n_layers, const slapo_
 }
 
 static int gemm_entry(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
-                      const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream, bool solo) {
+                      const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream, bool solo,
+                      void* ws, size_t ws_bytes) {
   if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_DGATE) return SLAPO_ERR_UNSUPPORTED;
   if (act != SLAPO_GELU_ERF && act != SLAPO_RELU) return SLAPO_ERR_UNSUPPORTED;
@@ -643,31 +659,47 @@ static int gemm_entry(int dtype, int layout, int epilogue, int act, int64_t M, i
   if (N % 8 || (epilogue == EPI_GATE && N % 16)) return SLAPO_ERR_ALIGN;
   if (layout == GEMM_TN ? (M % 8) : (K % 8)) return SLAPO_ERR_ALIGN;   // A's contiguous dimension
   if (layout == GEMM_NT && (K % 8)) return SLAPO_ERR_ALIGN;
-  if (misaligned(A) || misaligned(B) || misaligned(C)) return SLAPO_ERR_ALIGN;
+  if (misaligned(A) || misaligned(B) || misaligned(C) || misaligned(ws)) return SLAPO_ERR_ALIGN;
+  // a workspace is all or nothing: one that is too small for what the shape can use is refused, not half used
+  if (ws && ws_bytes < gemm_ws_bytes(dtype, epilogue, (int)M, (int)N, (int)K)) return SLAPO_ERR_WORKSPACE;
   entry_error();
   launch_gemm(dtype, layout, epilogue, act, (int)M, (int)N, (int)K, A, B, C, bias, aux_in, aux_out,
-              (hipStream_t)stream, solo);
+              (hipStream_t)stream, solo, (float*)ws, ws ? ws_bytes : 0);
   return finish();
 }
 
 int slapo_gemm(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
                const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
-  return gemm_entry(dtype, layout, epilogue, act, M, N, K, A, B, C, bias, aux_in, aux_out, stream, true);
+  return gemm_entry(dtype, layout, epilogue, act, M, N, K, A, B, C, bias, aux_in, aux_out, stream, true, nullptr, 0);
 }
 
-int slapo_gemm_shared(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
-                      const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, void* stream) {
-  return gemm_entry(dtype, layout, epilogue, act, M, N, K, A, B, C, bias, aux_in, aux_out, stream, false);
+int slapo_gemm_workspace(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, size_t* ws_bytes) {
+  if (!ws_bytes) return SLAPO_ERR_NULL;
+  if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
+  if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_DGATE) return SLAPO_ERR_UNSUPPORTED;
+  if (M <= 0 || N <= 0 || K <= 0) return SLAPO_ERR_SHAPE;
+  if (M * N >= ((int64_t)1 << 31) || M * K >= ((int64_t)1 << 31) || N * K >= ((int64_t)1 << 31)) return SLAPO_ERR_UNSUPPORTED;
+  *ws_bytes = gemm_ws_bytes(dtype, epilogue, (int)M, (int)N, (int)K);
+  return SLAPO_OK;
 }
 
-int slapo_gemm_kernel_name(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, int shared,
-                           int weight_grad, char* buf, size_t len) {
+int slapo_gemm_ex(int dtype, int layout, int epilogue, int act, int64_t M, int64_t N, int64_t K, const void* A,
+                  const void* B, void* C, const void* bias, const void* aux_in, void* aux_out, int flags, void* ws,
+                  size_t ws_bytes, void* stream) {
+  if (flags & ~SLAPO_GEMM_SHARED) return SLAPO_ERR_UNSUPPORTED;
+  return gemm_entry(dtype, layout, epilogue, act, M, N, K, A, B, C, bias, aux_in, aux_out, stream,
+                    !(flags & SLAPO_GEMM_SHARED), ws, ws_bytes);
+}
+
+int slapo_gemm_kernel_name(int dtype, int layout, int epilogue, int64_t M, int64_t N, int64_t K, int flags,
+                           int weight_grad, int with_ws, char* buf, size_t len) {
   if (!buf || len == 0) return SLAPO_ERR_NULL;
   if (dtype != SLAPO_BF16 && dtype != SLAPO_FP32 && dtype != SLAPO_FP16) return SLAPO_ERR_UNSUPPORTED;
   if (layout < GEMM_NT || layout > GEMM_TN || epilogue < EPI_NONE || epilogue > EPI_DGATE) return SLAPO_ERR_UNSUPPORTED;
+  if (flags & ~SLAPO_GEMM_SHARED) return SLAPO_ERR_UNSUPPORTED;
   if (M <= 0 || N <= 0 || K <= 0 || M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31)) return SLAPO_ERR_SHAPE;
   if (weight_grad && layout != GEMM_TN) return SLAPO_ERR_UNSUPPORTED;
-  describe_gemm(dtype, layout, epilogue, (int)M, (int)N, (int)K, !shared, weight_grad != 0, buf, len);
+  describe_gemm(dtype, layout, epilogue, (int)M, (int)N, (int)K, !(flags & SLAPO_GEMM_SHARED), weight_grad != 0, with_ws != 0, buf, len);
   return SLAPO_OK;
 }
 

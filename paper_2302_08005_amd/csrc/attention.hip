@@ -68,25 +68,13 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& v, int h) {
   w.z = pack2<F16>(v[8 * h + 4], v[8 * h + 5]); w.w = pack2<F16>(v[8 * h + 6], v[8 * h + 7]);
   return __builtin_bit_cast(bf16x8_t, w);
 }
-// acc += a b with the accumulator held in the accumulation registers (AGPRs). The dK/dV kernel of 128-wide heads
-// needs 128 registers for its two output accumulators alone; as ordinary registers they leave so few for
-// operands that fragments and the K/V operands are shuttled in and out of spill registers inside the loop. The
-// compiler's MFMA form is one choice per translation unit (here: results in ordinary registers, because
-// scores feed vector arithmetic), so these accumulations are written out. The instruction is opaque to the
-// compiler's hazard pass, hence the two wait states in front (vector-ALU write of an operand -> MFMA read);
-// waits for LDS reads are still inserted by the compiler (it tracks the operand registers), accumulations
-// into one register are at least four MFMAs apart in program order, and the caller waits before reading
-// the result with ordinary instructions (agpr_results_ready).
-template <bool F16>
-__device__ __forceinline__ void mfma16_agpr(f32x16_t& acc, bf16x8_t a, bf16x8_t b) {
-  if constexpr (F16) asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-  else asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
+// (mfma16_agpr, common.h: the dK/dV kernel of 128-wide heads needs 128 registers for its two output accumulators
+// alone; as ordinary registers they leave so few for operands that fragments and the K/V operands are shuttled in
+// and out of spill registers inside the loop. The operands of these accumulations are packed by vector
+// instructions right before, hence the default two wait states in front.)
 // The value exists in ordinary registers at this point of the program: an ordering anchor for operations that
 // have no side effects of their own (nothing is emitted).
 __device__ __forceinline__ void pin_here(f32x16_t& v) { asm volatile("" : "+v"(v)); }
-// more wait states than any MFMA needs before its result may be read by a non-MFMA instruction
-__device__ __forceinline__ void agpr_results_ready() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 // row index inside a 32x32 accumulator tile of register r
 __device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + 4 * (lane >> 5) + (r & 3); }
 

@@ -55,6 +55,25 @@ template <bool F16> __device__ __forceinline__ f32x16_t mfma16(bf16x8_t a, bf16x
   else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+// acc += a b with the accumulator held in the accumulation registers (AGPRs), written out because the compiler
+// picks one MFMA form per function and takes the ordinary registers whenever everything fits into 256 of them.
+// Opaque to the compiler's hazard pass: the caller makes sure that a and b were not written by a vector-ALU
+// instruction right before (NOPS wait states are emitted in front; LDS reads are tracked through the operand
+// registers and waited for by the compiler), that accumulations into one register are at least four MFMAs apart,
+// and calls agpr_results_ready() before reading the result with ordinary instructions.
+template <bool F16, int NOPS = 1>
+__device__ __forceinline__ void mfma16_agpr(f32x16_t& acc, bf16x8_t a, bf16x8_t b) {
+  if constexpr (NOPS > 0) {
+    if constexpr (F16) asm("s_nop %3\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b), "n"(NOPS - 1));
+    else asm("s_nop %3\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b), "n"(NOPS - 1));
+  } else {
+    if constexpr (F16) asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    else asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  }
+}
+// more wait states than any MFMA needs before its result may be read by a non-MFMA instruction
+__device__ __forceinline__ void agpr_results_ready() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 template <bool F16> __device__ __forceinline__ void load8h(const bf16_t* p, float (&v)[8]) {
   const uint4 w = *reinterpret_cast<const uint4*>(p);
   v[0] = unpack_lo<F16>(w.x); v[1] = unpack_hi<F16>(w.x); v[2] = unpack_lo<F16>(w.y); v[3] = unpack_hi<F16>(w.y);

@@ -115,15 +115,46 @@ __device__ __forceinline__ GateTerms gate_terms(float u, float w) {
 //     a 128x128 tile needs per slab keep that unit (64 B per clock) busy for as long as the slab's MFMAs
 //     take; with the loads on wavefronts of their own, that wait never stands in front of an MFMA.
 // F16: the 16-bit elements are IEEE half instead of bf16 (same data movement; MFMA and conversions differ).
+// Position of workgroup `bid` of a grid of tiles_m x tiles_n tiles. Workgroups are handed to the 8 XCDs round-robin;
+// the ids are renumbered so that each XCD (own L2) gets a run of consecutive tile ids, and the ids are ordered in
+// groups of 4 tile rows walked column by column, so that the tiles an XCD works on at the same time form a compact
+// block: its workgroups walk K in step, and every A (B) slab that reaches the L2 is used by all tiles of its row
+// (column) in the block. `copies`: the grid holds that many copies of the tile set (K ranges), copy after copy.
+struct TilePos { int tile_m, tile_n, copy; };
+__device__ __forceinline__ TilePos tile_position(int bid, int tiles_m, int tiles_n, int copies) {
+  const int nblk = tiles_m * tiles_n;
+  const int per_xcd = (nblk * copies) / 8;
+  if (bid < per_xcd * 8) bid = (bid & 7) * per_xcd + (bid >> 3);
+  TilePos t;
+  t.copy = bid / nblk;
+  bid -= t.copy * nblk;
+  constexpr int GROUP_M = 4;
+  const int group = bid / (GROUP_M * tiles_n);
+  const int first_m = group * GROUP_M;
+  const int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+  const int in_group = bid - group * GROUP_M * tiles_n;
+  t.tile_m = first_m + in_group % gsz;
+  t.tile_n = in_group / gsz;
+  return t;
+}
+
+// HYB: a grid whose tile count is not a multiple of the 256 CUs ends in a thin round that costs a full one. A
+// hybrid launch runs the tiles of the full rounds as usual (workgroups below tail_begin) and cuts each tile of
+// the remainder into tail_splits K ranges, one workgroup each, so that the last round is short instead of
+// thin: workgroup tail_begin + r * (tiles in the tail) + t covers range r of tail tile t and leaves its fp32
+// accumulators as a full tile in hyb_ws[(t * tail_splits + r)][BM][BN]; hybrid_reduce_kernel adds the ranges in
+// order and applies the epilogue. Plain launches pass tail_begin = number of tiles.
 template <int LAYOUT, int BM, int BN, int BK, int WGM, int WGN, int KS, int PF, int NS, int PW, bool KTAIL, int EPI,
-          bool F16 = false>
+          bool F16 = false, bool HYB = false>
 __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(int M, int N, int K,
                                                                   const bf16_t* __restrict__ A,
                                                                   const bf16_t* __restrict__ B,
                                                                   bf16_t* __restrict__ C,
                                                                   const bf16_t* __restrict__ bias,
                                                                   const bf16_t* aux_in,
-                                                                  bf16_t* __restrict__ aux_out, int act) {
+                                                                  bf16_t* __restrict__ aux_out, int act,
+                                                                  int tail_begin, int tail_splits,
+                                                                  float* __restrict__ hyb_ws) {
   constexpr bool A_KC = (LAYOUT != GEMM_TN);  // A operand contiguous along K
   constexpr bool DBUF = (LAYOUT == GEMM_TN);  // second fragment register set (measured: +7 % for TN, -4 % NN, -1 % NT)
   constexpr bool B_KC = (LAYOUT == GEMM_NT);
@@ -161,28 +192,27 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   bf16_t* sA = smem;               // [NSTG][SA]
   bf16_t* sB = smem + NSTG * SA;   // [NSTG][SB]
 
-  // Workgroups are handed to the 8 XCDs round-robin. Renumber them so that each XCD (own L2) gets a
-  // run of consecutive tile ids, and order the ids in groups of 4 tile rows walked column by column, so
-  // that the tiles an XCD works on at the same time form a compact block: its workgroups walk K in step,
-  // and every A (B) slab that reaches the L2 is used by all tiles of its row (column) in the block.
   const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
   const int nblk = tiles_m * tiles_n;
   // Split-K instances: `act` K ranges per tile, every (range, tile) pair a workgroup; consecutive ids walk the
   // tiles of one range, so the blocks an XCD holds still share operand panels.
   constexpr bool SPLITK = (EPI == EPI_SPLITK);
   static_assert(!SPLITK || NS > 0, "split-K instances use the direct-load pipeline");
-  const int splits = SPLITK ? act : 1;
+  static_assert(!(HYB && SPLITK) && (!HYB || NS > 0), "hybrid launches use the direct-load pipeline");
   int bid = blockIdx.x;
-  const int per_xcd = (nblk * splits) / 8;
-  if (bid < per_xcd * 8) bid = (bid & 7) * per_xcd + (bid >> 3);
-  const int split = SPLITK ? bid / nblk : 0;
-  if (SPLITK) bid -= split * nblk;
-  constexpr int GROUP_M = 4;
-  const int group = bid / (GROUP_M * tiles_n);
-  const int first_m = group * GROUP_M;
-  const int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
-  const int in_group = bid - group * GROUP_M * tiles_n;
-  const int tile_m = first_m + in_group % gsz, tile_n = in_group / gsz;
+  bool is_tail = false;          // (uniform for the workgroup)
+  int tail_range = 0, tail_tile = 0;
+  if (HYB && bid >= tail_begin) {
+    const int t = bid - tail_begin, tail_tiles = nblk - tail_begin;
+    tail_range = t / tail_tiles;
+    tail_tile = t - tail_range * tail_tiles;
+    bid = tail_begin + tail_tile;
+    is_tail = true;
+  }
+  const TilePos pos = tile_position(bid, tiles_m, tiles_n, SPLITK ? act : 1);
+  const int splits = SPLITK ? act : (is_tail ? tail_splits : 1);
+  const int split = SPLITK ? pos.copy : tail_range;
+  const int tile_m = pos.tile_m, tile_n = pos.tile_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int lane = threadIdx.x & 63;
@@ -229,8 +259,8 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   // slabs of this workgroup: all of them, or the split's range (the host makes every range non-empty)
   const int nk_all = (K + BK - 1) / BK;
   const int nk_per = (nk_all + splits - 1) / splits;
-  const int ks0 = SPLITK ? split * nk_per : 0;
-  const int nk = SPLITK ? (nk_all - ks0 < nk_per ? nk_all - ks0 : nk_per) : nk_all;
+  const int ks0 = split * nk_per;   // (split = 0, splits = 1 for workgroups that walk all of K)
+  const int nk = nk_all - ks0 < nk_per ? nk_all - ks0 : nk_per;
   static_assert(PF == 1 || PF == 2, "register prefetch depth");
   u32x4_t ra0[A_LOADS], rb0[B_LOADS], ra1[A_LOADS], rb1[B_LOADS];   // register sets: slab k lives in set k % PF
   // Every call issues exactly A_LOADS + B_LOADS loads (slab index clamped to the last one), so the number
@@ -531,10 +561,10 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
 #pragma unroll
     for (int e = 0; e < 4; ++e) { u[2 * e] = unpack_lo<F16>(w[e]); u[2 * e + 1] = unpack_hi<F16>(w[e]); }
   };
-  if (AUX) aux_fetch(0, au[0]);
+  if (AUX && !is_tail) aux_fetch(0, au[0]);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    if (AUX && i + 1 < TM) aux_fetch(i + 1, au[i + 1]);
+    if (AUX && !is_tail && i + 1 < TM) aux_fetch(i + 1, au[i + 1]);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -550,7 +580,11 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
       const float4 lo = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8);
       const float4 hi = *reinterpret_cast<const float4*>(stage + row * LDP + cc * 8 + 4);
       v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-      if (m < M && n < N) {
+      if (HYB && is_tail) {   // one K range of a tail tile: the bare accumulators, as a full tile of the workspace
+        float* part = hyb_ws + ((size_t)(tail_tile * tail_splits + tail_range) * BM + (wm0 + i * 32 + row)) * BN + wn0 + cc * 8;
+        *reinterpret_cast<float4*>(part) = lo;
+        *reinterpret_cast<float4*>(part + 4) = hi;
+      } else if (m < M && n < N) {
         const int64_t idx = (int64_t)m * N + n;
         if (EPI == EPI_BIAS) {
 #pragma unroll
@@ -710,7 +744,7 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
       (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
       hipLaunchKernelGGL(kern, dim3(tiles), dim3((WGM * WGN * KS + PW) * 64), lds, st, M, N, K, (const bf16_t*)A,       \
                          (const bf16_t*)B, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)aux_in,          \
-                         (bf16_t*)aux_out, act);                                                            \
+                         (bf16_t*)aux_out, act, tiles, 1, (float*)nullptr);                                 \
     } else {                                                                                                \
       launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 1, 1, 0, 0, true, F16>(epi, act, M, N, K, A, B, C, bias, aux_in,    \
                                                               aux_out, st);                                 \
@@ -726,6 +760,87 @@ static void launch_bf16_tile(int epi, int act, int M, int N, int K, const void* 
     default: SLAPO_GEMM(EPI_ADD); break;
   }
 #undef SLAPO_GEMM
+}
+
+// ---- thin last rounds: the tail tiles of a 256x256 grid in several K ranges ----------------------------
+// 320 tiles on 256 CUs take two rounds for 1.25 rounds of work. With a workspace at hand, the tiles beyond the
+// last full round are cut into s = 256 / (their number) K ranges, so that the last round has about 256 workgroups
+// of 1/s the length, and a second kernel adds the ranges in order (bitwise reproducible) and applies the
+// epilogue. Worth it when the saved (1 - 1/s) of a round outweighs writing and re-reading the partial tiles,
+// i.e. for long K; plain and add epilogues only (the others have so many tiles that a thin round matters little).
+struct HybridPlan { int tail_begin, tail_tiles, splits; size_t ws_bytes; };
+static HybridPlan hybrid_plan(int epi, int M, int N, int K) {
+  const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  HybridPlan none = {tiles, 0, 1, 0}, p = none;
+  static const bool disabled = debug_flag("no-hybrid");
+  if (disabled || (epi != EPI_NONE && epi != EPI_ADD) || K % 128 != 0) return none;
+  const int rem = tiles % 256, nk = K / 64;
+  if (tiles <= 256 || rem == 0) return none;
+  int s = 256 / rem;
+  s = s > 8 ? 8 : s;
+  while (s > 1 && ((s - 1) * ((nk + s - 1) / s) >= nk || nk / s < 8)) --s;   // every range non-empty, at least 8 slabs
+  if (s < 2) return none;
+  // a round of 64-deep slabs takes about 1.1 us per slab; the partial tiles are written and read once at ~4 TB/s
+  const double saved_us = (1.0 - 1.0 / s) * nk * 1.1;
+  const double cost_us = 2.0 * rem * s * 256.0 * 256.0 * 4.0 / 4.0e6;
+  if (saved_us < 1.5 * cost_us) return none;
+  p.tail_tiles = rem;
+  p.tail_begin = tiles - rem;
+  p.splits = s;
+  p.ws_bytes = (size_t)rem * s * 256 * 256 * sizeof(float);
+  return p;
+}
+
+// C tile of tail tile t = sum over the K ranges of hyb_ws[(t * splits + r)] (+ aux_in), eight columns per thread.
+template <bool F16>
+__global__ __launch_bounds__(256) void hybrid_reduce_kernel(int M, int N, int tail_begin, int splits,
+                                                            const float* __restrict__ ws, bf16_t* C,
+                                                            const bf16_t* aux_in) {
+  constexpr int BM = 256, BN = 256, CPT = BM * BN / 8;   // 8-column chunks per tile
+  const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  const int t = q / CPT, in_tile = q - t * CPT;
+  const TilePos pos = tile_position(tail_begin + t, tiles_m, tiles_n, 1);
+  const int row = in_tile / (BN / 8), col = (in_tile % (BN / 8)) * 8;
+  const int m = pos.tile_m * BM + row, n = pos.tile_n * BN + col;
+  if (m >= M || n >= N) return;
+  const float* part = ws + ((size_t)t * splits * BM + row) * BN + col;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < splits; ++r) {
+    float v[8];
+    load8(part + (size_t)r * BM * BN, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+  const int64_t idx = (int64_t)m * N + n;
+  if (aux_in) {
+    float v[8];
+    load8h<F16>(aux_in + idx, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+  store8h<F16>(C + idx, acc);
+}
+
+template <int LAYOUT, bool F16>
+static void launch_hybrid(const HybridPlan& hp, int epi, int M, int N, int K, const void* A, const void* B, void* C,
+                          const void* aux_in, float* ws, hipStream_t st) {
+  constexpr int BM = 256, BN = 256;
+  const size_t lds = gemm_lds_bytes<BM, BN, 64, 2, 4, 1, 2>();
+  const int grid = hp.tail_begin + hp.tail_tiles * hp.splits;
+#define SLAPO_HYB(E)                                                                                           \
+  do {                                                                                                         \
+    auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, 64, 2, 4, 1, 2, 2, 0, false, E, F16, true>;                   \
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);       \
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B,      \
+                       (bf16_t*)C, (const bf16_t*)nullptr, (const bf16_t*)aux_in, (bf16_t*)nullptr, 0,         \
+                       hp.tail_begin, hp.splits, ws);                                                          \
+  } while (0)
+  if (epi == EPI_ADD) SLAPO_HYB(EPI_ADD); else SLAPO_HYB(EPI_NONE);
+#undef SLAPO_HYB
+  const int chunks = hp.tail_tiles * (BM * BN / 8);
+  hipLaunchKernelGGL(hybrid_reduce_kernel<F16>, dim3(chunks / 256), dim3(256), 0, st, M, N, hp.tail_begin, hp.splits,
+                     (const float*)ws, (bf16_t*)C, epi == EPI_ADD ? (const bf16_t*)aux_in : (const bf16_t*)nullptr);
 }
 
 // Tile selection, from measurements on the layer's shapes. 256x256 tiles (8 wavefronts, 128x64 each, direct
@@ -765,7 +880,17 @@ static TileKind select_tile(int layout, int M, int N, int K, bool solo) {
 
 template <int LAYOUT, bool F16>
 static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
-                        const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo) {
+                        const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo, float* ws,
+                        size_t ws_bytes) {
+  if (ws && select_tile(LAYOUT, M, N, K, solo) == TILE_256) {
+    // (a GEMM that runs alone and does better with a full grid of 128x128 tiles keeps those: measured 401 against
+    // 415 us for the 8192 x 2560 x 10240 product)
+    const HybridPlan hp = hybrid_plan(epi, M, N, K);
+    if (hp.ws_bytes && hp.ws_bytes <= ws_bytes) {
+      launch_hybrid<LAYOUT, F16>(hp, epi, M, N, K, A, B, C, aux_in, ws, st);
+      return;
+    }
+  }
   switch (select_tile(LAYOUT, M, N, K, solo)) {
     case TILE_256:
       launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
@@ -824,9 +949,14 @@ static int weight_grad_splits(int M, int N, int K) {
   return s < 2 ? 1 : (int)s;
 }
 
+size_t gemm_ws_bytes(int dtype, int epi, int M, int N, int K) {
+  return dtype == DT_FP32 ? 0 : hybrid_plan(epi, M, N, K).ws_bytes;
+}
+
 size_t weight_grad_ws_bytes(int dtype, int M, int N, int K) {
-  const int s = dtype == DT_FP32 ? 1 : weight_grad_splits(M, N, K);
-  return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
+  if (dtype == DT_FP32) return 0;
+  const int s = weight_grad_splits(M, N, K);
+  return s > 1 ? (size_t)s * M * N * sizeof(float) : hybrid_plan(EPI_NONE, M, N, K).ws_bytes;   // (same for the add epilogue)
 }
 
 template <bool F16>
@@ -839,7 +969,7 @@ static void launch_splitk(int splits, int accumulate, int M, int N, int K, const
   (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3((2 * 2 * 2 + 4) * 64), lds, st, M, N, K, (const bf16_t*)A,
                      (const bf16_t*)B, (bf16_t*)C, (const bf16_t*)nullptr, (const bf16_t*)nullptr,
-                     reinterpret_cast<bf16_t*>(ws), splits);
+                     reinterpret_cast<bf16_t*>(ws), splits, tiles * splits, 1, (float*)nullptr);
   const int64_t mn = (int64_t)M * N, chunks = mn / 8;
   const dim3 grid((unsigned)((chunks + 255) / 256));
   if (F16) hipLaunchKernelGGL(splitk_reduce_kernel<f16_t>, grid, dim3(256), 0, st, chunks, mn, splits, ws, (f16_t*)C, accumulate);
@@ -851,7 +981,7 @@ void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const vo
   const int splits = (ws && dtype != DT_FP32) ? weight_grad_splits(M, N, K) : 1;
   if (splits == 1) {
     launch_gemm(dtype, GEMM_TN, accumulate ? EPI_ADD : EPI_NONE, 0, M, N, K, A, B, C, nullptr, accumulate ? C : nullptr,
-                nullptr, st, solo);
+                nullptr, st, solo, ws, ws ? weight_grad_ws_bytes(dtype, M, N, K) : 0);
     return;
   }
   if (dtype == DT_FP16) launch_splitk<true>(splits, accumulate, M, N, K, A, B, C, ws, st);
@@ -861,10 +991,19 @@ void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const vo
 // The kernel instance a GEMM of this shape runs as, in the spelling of the kernel's template arguments
 // (layout, BM, BN, BK, WGM, WGN, KS, PF, NS, PW, KTAIL, epilogue, F16), as the profiler prints the symbol; for
 // the weight-gradient path (`weight_grad`) with its K ranges, if any.
-void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool solo, bool weight_grad, char* buf, size_t len) {
+void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool solo, bool weight_grad, bool with_ws,
+                   char* buf, size_t len) {
   if (dtype == DT_FP32) { snprintf(buf, len, "gemm_f32_kernel<%d>", layout); return; }
   const int f16 = dtype == DT_FP16 ? 1 : 0;
   const char* b = f16 ? "true" : "false";
+  if (with_ws && !(weight_grad && weight_grad_splits(M, N, K) > 1) && select_tile(layout, M, N, K, solo) == TILE_256) {
+    const HybridPlan hp = hybrid_plan(weight_grad ? EPI_NONE : epi, M, N, K);
+    if (hp.ws_bytes) {
+      snprintf(buf, len, "gemm_bf16_kernel<%d, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, %d, %s, true> (%d tiles + %d tiles in %d K ranges) + hybrid_reduce_kernel",
+               layout, epi, b, hp.tail_begin, hp.tail_tiles, hp.splits);
+      return;
+    }
+  }
   if (weight_grad) {
     const int splits = weight_grad_splits(M, N, K);
     if (splits > 1) {
@@ -882,7 +1021,8 @@ void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool sol
 }
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
-                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo) {
+                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo, float* ws,
+                 size_t ws_bytes) {
   if (dtype == DT_FP32) {
     dim3 grid((N + 63) / 64, (M + 63) / 64);
 #define SLAPO_F32(L)                                                                                      \
@@ -895,9 +1035,9 @@ void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, c
     return;
   }
 #define SLAPO_H(F)                                                                                          \
-  if (layout == GEMM_NT) launch_bf16<GEMM_NT, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo);     \
-  else if (layout == GEMM_NN) launch_bf16<GEMM_NN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo); \
-  else launch_bf16<GEMM_TN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo)
+  if (layout == GEMM_NT) launch_bf16<GEMM_NT, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo, ws, ws_bytes);     \
+  else if (layout == GEMM_NN) launch_bf16<GEMM_NN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo, ws, ws_bytes); \
+  else launch_bf16<GEMM_TN, F>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st, solo, ws, ws_bytes)
   if (dtype == DT_FP16) { SLAPO_H(true); } else { SLAPO_H(false); }
 #undef SLAPO_H
 }

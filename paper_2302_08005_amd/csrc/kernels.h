@@ -18,12 +18,18 @@ enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
 enum { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_ACT = 2, EPI_DACT = 3, EPI_ADD = 4, EPI_GATE = 5, EPI_DGATE = 6, EPI_SPLITK = 7 };
 
 // solo: nothing else runs beside this GEMM (it may then pick tiles by round count, see launch_bf16)
+// ws / ws_bytes: optional fp32 workspace (gemm_ws_bytes says how much a shape can use; 0: none). With it, a grid
+//   of 256x256 tiles that would end in a thin last round computes its last tiles in several K ranges instead.
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
-                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo = false);
-void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool solo, bool weight_grad, char* buf, size_t len);
+                 void* C, const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo = false,
+                 float* ws = nullptr, size_t ws_bytes = 0);
+size_t gemm_ws_bytes(int dtype, int epi, int M, int N, int K);
+void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool solo, bool weight_grad, bool with_ws,
+                   char* buf, size_t len);
 // Weight gradient C[M,N] (+)= A[K,M]^T B[K,N] (accumulate: add to C). Outputs with too few tiles to fill the
 // chip are computed in several K ranges at once (fp32 partial tiles in `ws`, summed in range order by a second
-// kernel: deterministic); weight_grad_ws_bytes says how much workspace a shape wants (0: none, plain GEMM).
+// kernel: deterministic), outputs whose tile grid ends in a thin round have their last tiles cut into K ranges
+// (launch_gemm); weight_grad_ws_bytes says how much workspace a shape wants (0: none, plain GEMM).
 size_t weight_grad_ws_bytes(int dtype, int M, int N, int K);
 void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const void* A, const void* B, void* C,
                         float* ws, hipStream_t st, bool solo = false);

@@ -181,3 +181,22 @@ def test_static_scratch_bound_and_argument_checks():
     assert lib.slapo_weight_grad_static(0, 0, 1024, 1020, 16384, 4096, 4096, 4096, None) == -4
     assert lib.slapo_weight_grad_static(0, 0, 0, 1024, 16384, 4096, 4096, 4096, None) == -2
     assert lib.slapo_weight_grad_static(9, 0, 1024, 1024, 16384, 4096, 4096, 4096, None) == -3
+
+
+def test_gemm_workspace_rules_on_the_host():
+    """The K-range treatment of thin last rounds: which shapes ask for a workspace, and the too-small refusal."""
+    lib = B.lib()
+    # 8192 x 2560 outputs are 320 tiles of 256 x 256: 64 tail tiles in 4 K ranges when K is long ...
+    assert B.slapo_gemm_workspace(B.BF16, B.NN, B.EPI_NONE, 8192, 2560, 10240) == 64 * 4 * 256 * 256 * 4
+    assert "256 tiles + 64 tiles in 4 K ranges" in B.slapo_gemm_kernel_name(B.BF16, B.NN, B.EPI_NONE, 8192, 2560, 10240, flags=B.GEMM_SHARED, with_ws=1)
+    # ... nothing for short K (the partial tiles would cost more than the thin round), full rounds, other epilogues, fp32
+    assert B.slapo_gemm_workspace(B.BF16, B.NN, B.EPI_NONE, 8192, 2560, 1024) == 0
+    assert B.slapo_gemm_workspace(B.BF16, B.NT, B.EPI_NONE, 8192, 2048, 8192) == 0
+    assert B.slapo_gemm_workspace(B.BF16, B.NT, B.EPI_BIAS_ACT, 8192, 2560, 10240) == 0
+    assert B.slapo_gemm_workspace(B.FP32, B.NN, B.EPI_NONE, 8192, 2560, 10240) == 0
+    need = B.slapo_gemm_workspace(B.BF16, B.NN, B.EPI_NONE, 8192, 2560, 10240)
+    args = (0, 1, 0, 0, 8192, 2560, 10240, 4096, 4096, 4096, None, None, None, 0)
+    assert lib.slapo_gemm_ex(*args, 4096, need - 16, None) == -5      # before any device work
+    assert lib.slapo_gemm_ex(*args, 4096 + 8, need, None) == -4
+    assert lib.slapo_gemm_ex(*args[:13], 2, 4096, need, None) == -3   # unknown flag
+    assert B.status_string(-5).startswith("shape needs more workspace")

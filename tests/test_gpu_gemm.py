@@ -102,3 +102,42 @@ def test_weight_gradient_in_k_ranges(dtype, M, N, K, split):
     plain = torch.empty_like(out)                    # the one-range kernel: same product, other summation order
     B.slapo_gemm(dtype, B.TN, B.EPI_NONE, 0, M, N, K, A, Bt, plain)
     assert err(plain, to_np(out)) <= tol
+
+
+# Grids of 256x256 tiles that end in a thin round (272 and 289 tiles on 256 CUs, ragged edges in the second case):
+# with a workspace the tiles beyond the full round are computed in several K ranges and added by a second kernel.
+@pytest.mark.parametrize("dtype", [W.BF16, W.FP16])
+@pytest.mark.parametrize("layout", [B.NT, B.NN, B.TN])
+@pytest.mark.parametrize("M,N,K", [(4352, 4096, 2048), (4296, 4200, 3072)])
+def test_thin_last_round_in_k_ranges(dtype, layout, M, N, K):
+    nbytes = B.slapo_gemm_workspace(dtype, layout, B.EPI_NONE, M, N, K)
+    assert nbytes > 0 and nbytes == B.slapo_gemm_workspace(dtype, layout, B.EPI_ADD, M, N, K)
+    assert B.slapo_gemm_workspace(dtype, layout, B.EPI_BIAS, M, N, K) == 0          # plain and add epilogues only
+    assert B.slapo_gemm_workspace(dtype, layout, B.EPI_NONE, 4096, 4096, K) == 0     # a full round: nothing to do
+    assert "K ranges" in B.slapo_gemm_kernel_name(dtype, layout, B.EPI_NONE, M, N, K, flags=B.GEMM_SHARED, with_ws=1)
+    rng = np.random.default_rng(M + N + K + layout)
+    a = store(rng.standard_normal((M, K)), dtype)
+    b = store(rng.standard_normal((K, N)) * 0.1, dtype)
+    aux = store(rng.standard_normal((M, N)), dtype)
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    A = to_dev(a if layout != B.TN else a.T.copy(), dtype)
+    Bm = to_dev(b.T.copy() if layout == B.NT else b, dtype)
+    auxd = to_dev(aux, dtype)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    out = torch.empty(M, N, dtype=A.dtype, device=DEV)
+    B.slapo_gemm_ex(dtype, layout, B.EPI_NONE, 0, M, N, K, A, Bm, out, ws=ws, flags=B.GEMM_SHARED)
+    tol = {W.BF16: 5e-3, W.FP16: 1e-3}[dtype]
+    assert err(out, ref) <= tol
+    ws.fill_(0x7F)                                   # stale workspace contents must not matter
+    out2 = torch.empty_like(out)
+    B.slapo_gemm_ex(dtype, layout, B.EPI_NONE, 0, M, N, K, A, Bm, out2, ws=ws, flags=B.GEMM_SHARED)
+    assert torch.equal(out, out2)                    # bit for bit, whichever workgroup finishes first
+    plain = torch.empty_like(out)                    # without a workspace: every tile in one piece
+    B.slapo_gemm(dtype, layout, B.EPI_NONE, 0, M, N, K, A, Bm, plain)
+    assert err(plain, to_np(out)) <= tol and not torch.equal(plain, out)   # (the tail tiles sum in another order)
+    acc = auxd.clone()                               # add epilogue, in place
+    B.slapo_gemm_ex(dtype, layout, B.EPI_ADD, 0, M, N, K, A, Bm, acc, aux_in=acc, ws=ws, flags=B.GEMM_SHARED)
+    assert err(acc, ref + aux) <= tol
+    with pytest.raises(B.SlapoError) as e:           # a workspace that is too small is refused, not half used
+        B.slapo_gemm_ex(dtype, layout, B.EPI_NONE, 0, M, N, K, A, Bm, out, ws=ws[:nbytes // 2])
+    assert e.value.status == -5
