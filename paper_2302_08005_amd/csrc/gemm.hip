@@ -989,7 +989,7 @@ void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const vo
 }
 
 // The kernel instance a GEMM of this shape runs as, in the spelling of the kernel's template arguments
-// (layout, BM, BN, BK, WGM, WGN, KS, PF, NS, PW, KTAIL, epilogue, F16), as the profiler prints the symbol; for
+// (layout, BM, BN, BK, WGM, WGN, KS, PF, NS, PW, KTAIL, epilogue, F16, HYB), as the profiler prints the symbol; for
 // the weight-gradient path (`weight_grad`) with its K ranges, if any.
 void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool solo, bool weight_grad, bool with_ws,
                    char* buf, size_t len) {
@@ -1007,7 +1007,7 @@ void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool sol
   if (weight_grad) {
     const int splits = weight_grad_splits(M, N, K);
     if (splits > 1) {
-      snprintf(buf, len, "gemm_bf16_kernel<2, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, %d, %s> in %d K ranges + splitk_reduce_kernel", EPI_SPLITK, b, splits);
+      snprintf(buf, len, "gemm_bf16_kernel<2, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, %d, %s, false> in %d K ranges + splitk_reduce_kernel", EPI_SPLITK, b, splits);
       return;
     }
   }
@@ -1017,7 +1017,7 @@ void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool sol
                                       "128, 128, 64, 2, 2, 1, 1, 0, 0, true"};
   TileKind k = select_tile(layout, M, N, K, solo);
   if (k != TILE_GENERAL && !epi_used(layout, epi)) k = TILE_GENERAL;   // epilogues the layer never pairs with this layout
-  snprintf(buf, len, "gemm_bf16_kernel<%d, %s, %d, %s>", layout, shape[(int)k], epi, b);
+  snprintf(buf, len, "gemm_bf16_kernel<%d, %s, %d, %s, false>", layout, shape[(int)k], epi, b);
 }
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,

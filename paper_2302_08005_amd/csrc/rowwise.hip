@@ -412,16 +412,20 @@ __global__ __launch_bounds__(256) void colsum_partials_kernel(int64_t rows, int6
   }
 }
 
-// stage 2: out[n] = sum_i partials[i*stride + n]. A block owns 64 columns; its 16 wavefronts each sum a
-// contiguous share of the rows with all loads in flight at once, then the shares are added in wave order.
+// stage 2: out[n] = sum_i partials[i*stride + n]. A block owns 64 columns; its RW wavefronts each sum a
+// contiguous share of the rows with eight loads in flight at once, then the shares are added in wave order.
+// Four wavefronts per block: these kernels run between the GEMMs of the backward pass, whose workgroups leave a
+// CU room for a few more wavefronts but never for a block of sixteen (which waited for a CU to fall idle: 84 us
+// in the step against 4 us alone).
+constexpr int RW = 4;
 template <typename T>
-__global__ __launch_bounds__(1024) void colreduce_partials_kernel(int64_t nblk, int64_t stride, int64_t N,
+__global__ __launch_bounds__(RW * 64) void colreduce_partials_kernel(int64_t nblk, int64_t stride, int64_t N,
                                                                   const float* __restrict__ partials,
                                                                   T* __restrict__ out, int accumulate) {
-  __shared__ float red[16][64];
+  __shared__ float red[RW][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t n = (int64_t)blockIdx.x * 64 + lane;
-  const int64_t per = (nblk + 15) / 16;
+  const int64_t per = (nblk + RW - 1) / RW;
   const int64_t i0 = wave * per, i1 = (i0 + per < nblk) ? i0 + per : nblk;
   float s = 0.f;
   if (n < N) {
@@ -440,7 +444,7 @@ __global__ __launch_bounds__(1024) void colreduce_partials_kernel(int64_t nblk, 
   if (wave == 0 && n < N) {
     float t = red[0][lane];
 #pragma unroll
-    for (int w = 1; w < 16; ++w) t += red[w][lane];
+    for (int w = 1; w < RW; ++w) t += red[w][lane];
     if (accumulate) t += to_f32(out[n]);
     from_f32(out[n], t);
   }
@@ -579,21 +583,21 @@ void launch_colsum_partials(int dtype, int64_t rows, int64_t N, const void* a, f
 void launch_colreduce_partials(int dtype, int64_t nblk, int64_t stride, int64_t N, const float* partials,
                                void* out, int accumulate, hipStream_t st) {
   dim3 grid((unsigned)((N + 63) / 64));
-  if (dtype == DT_FP32) hipLaunchKernelGGL(colreduce_partials_kernel<float>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (float*)out, accumulate);
-  else if (dtype == DT_FP16) hipLaunchKernelGGL(colreduce_partials_kernel<f16_t>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (f16_t*)out, accumulate);
-  else hipLaunchKernelGGL(colreduce_partials_kernel<bf16_t>, grid, dim3(1024), 0, st, nblk, stride, N, partials, (bf16_t*)out, accumulate);
+  if (dtype == DT_FP32) hipLaunchKernelGGL(colreduce_partials_kernel<float>, grid, dim3(RW * 64), 0, st, nblk, stride, N, partials, (float*)out, accumulate);
+  else if (dtype == DT_FP16) hipLaunchKernelGGL(colreduce_partials_kernel<f16_t>, grid, dim3(RW * 64), 0, st, nblk, stride, N, partials, (f16_t*)out, accumulate);
+  else hipLaunchKernelGGL(colreduce_partials_kernel<bf16_t>, grid, dim3(RW * 64), 0, st, nblk, stride, N, partials, (bf16_t*)out, accumulate);
 }
 
 // the three partial rows (dgamma, dbeta, dbias) of the fused backward kernel in one launch
 template <typename T>
-__global__ __launch_bounds__(1024) void colreduce3_kernel(int64_t nblk, int H, const float* __restrict__ partials,
+__global__ __launch_bounds__(RW * 64) void colreduce3_kernel(int64_t nblk, int H, const float* __restrict__ partials,
                                                           T* out0, T* out1, T* out2, int accumulate) {
-  __shared__ float red[16][64];
+  __shared__ float red[RW][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, which = blockIdx.y;
   T* out = which == 0 ? out0 : (which == 1 ? out1 : out2);
   if (out == nullptr) return;   // uniform for the block
   const int64_t n = (int64_t)blockIdx.x * 64 + lane;
-  const int64_t per = (nblk + 15) / 16;
+  const int64_t per = (nblk + RW - 1) / RW;
   const int64_t i0 = wave * per, i1 = (i0 + per < nblk) ? i0 + per : nblk;
   const float* src = partials + (int64_t)which * H;
   const int64_t stride = 3 * (int64_t)H;
@@ -614,7 +618,7 @@ __global__ __launch_bounds__(1024) void colreduce3_kernel(int64_t nblk, int H, c
   if (wave == 0 && n < H) {
     float t = red[0][lane];
 #pragma unroll
-    for (int w = 1; w < 16; ++w) t += red[w][lane];
+    for (int w = 1; w < RW; ++w) t += red[w][lane];
     if (accumulate) t += to_f32(out[n]);
     from_f32(out[n], t);
   }
@@ -623,9 +627,9 @@ __global__ __launch_bounds__(1024) void colreduce3_kernel(int64_t nblk, int H, c
 void launch_colreduce3(int dtype, int64_t nblk, int H, const float* partials, void* out0, void* out1, void* out2,
                        int accumulate, hipStream_t st) {
   dim3 grid((unsigned)((H + 63) / 64), 3);
-  if (dtype == DT_FP32) hipLaunchKernelGGL(colreduce3_kernel<float>, grid, dim3(1024), 0, st, nblk, H, partials, (float*)out0, (float*)out1, (float*)out2, accumulate);
-  else if (dtype == DT_FP16) hipLaunchKernelGGL(colreduce3_kernel<f16_t>, grid, dim3(1024), 0, st, nblk, H, partials, (f16_t*)out0, (f16_t*)out1, (f16_t*)out2, accumulate);
-  else hipLaunchKernelGGL(colreduce3_kernel<bf16_t>, grid, dim3(1024), 0, st, nblk, H, partials, (bf16_t*)out0, (bf16_t*)out1, (bf16_t*)out2, accumulate);
+  if (dtype == DT_FP32) hipLaunchKernelGGL(colreduce3_kernel<float>, grid, dim3(RW * 64), 0, st, nblk, H, partials, (float*)out0, (float*)out1, (float*)out2, accumulate);
+  else if (dtype == DT_FP16) hipLaunchKernelGGL(colreduce3_kernel<f16_t>, grid, dim3(RW * 64), 0, st, nblk, H, partials, (f16_t*)out0, (f16_t*)out1, (f16_t*)out2, accumulate);
+  else hipLaunchKernelGGL(colreduce3_kernel<bf16_t>, grid, dim3(RW * 64), 0, st, nblk, H, partials, (bf16_t*)out0, (bf16_t*)out1, (bf16_t*)out2, accumulate);
 }
 
 void launch_dropout_mask(int64_t n_elements, uint8_t* mask, const DropoutParams& dp, hipStream_t st) {
