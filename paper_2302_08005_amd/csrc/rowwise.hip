@@ -391,9 +391,26 @@ __global__ __launch_bounds__(256) void colsum_partials_kernel(int64_t rows, int6
   const int64_t r0 = (int64_t)blockIdx.y * per, r1 = (r0 + per < rows) ? r0 + per : rows;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (chunk * 8 < N) {
-    for (int64_t rr = r0 + ry; rr < r1; rr += 8) {
+    // eight rows' loads go out before the first is added (one load in flight per thread left the kernel bound by
+    // memory latency: 92 us for 134 MB); the rows are added in the order of the plain loop, so the sums keep their bits
+    constexpr int U = 8;
+    const T* p = a + chunk * 8;
+    int64_t rr = r0 + ry;
+    for (; rr + 8 * (U - 1) < r1; rr += 8 * U) {
+      Raw8<T> raw[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) raw[u].load(p + (rr + 8 * u) * N);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float v[8];
+        raw[u].get(v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += v[j];
+      }
+    }
+    for (; rr < r1; rr += 8) {
       float v[8];
-      load8(a + rr * N + chunk * 8, v);
+      load8(p + rr * N, v);
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[j] += v[j];
     }
