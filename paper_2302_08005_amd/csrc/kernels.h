@@ -36,6 +36,7 @@ void launch_weight_grad(int dtype, int accumulate, int M, int N, int K, const vo
 
 struct AttnShape {
   int batch, seq, hidden, heads, causal;
+  int lpt_heads = 0;   // causal block order: heads per longest-first group (set by the launchers; 0 = head by head)
   // dropout on the attention probabilities (site 2; element ((b*heads + a)*seq + i)*seq + j); thr == 0: none
   DropoutParams drop = {0u, 0u, 2u, 0u, 0u, 1.0f};
 };
