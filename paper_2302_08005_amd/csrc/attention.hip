@@ -107,7 +107,7 @@ struct TileDirect {
 #pragma unroll
     for (int k = 0; k < MINE; ++k) {
       const int instr = wave + 4 * k;
-      if (instr < SPR) buffer_load_lds_16(base, bytes, tile + instr * 512, voff[k], row0_bytes);
+      if (instr < SPR) buffer_load_lds_16_untracked(base, bytes, tile + instr * 512, voff[k], row0_bytes);
     }
   }
 };

@@ -152,6 +152,32 @@ __device__ __forceinline__ void buffer_load_lds_16(const void* base, unsigned by
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds, 16, voffset, soffset, 0, 0);
 }
 
+// The same load, issued where the compiler does not see it. The compiler orders every LDS read it cannot tell apart
+// from a pending direct load behind that load: plain LDS reads pass, but in front of every transposing read
+// (ds_read_b64_tr_b16) that follows a direct load it waits for ALL outstanding vector-memory loads, i.e. for the tile
+// that was just requested for a later step, which undoes the prefetch. Kernels that mix the two issue their direct
+// loads through this form and keep the landing of every tile under their own counter waits (wait_loads_and_lds in
+// front of the barrier that hands a tile over), which they need in either form. M0 carries the LDS address; one wait
+// state between writing it and the load that reads it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void buffer_load_lds_16_untracked(const void* base, unsigned bytes, void* lds,
+                                                             unsigned voffset, unsigned soffset) {
+  typedef int i32x4_t __attribute__((ext_vector_type(4)));
+  const unsigned long long a = (unsigned long long)base;
+  i32x4_t rsrc;   // the resource words of buffer_load_lds_16
+  rsrc[0] = (int)(unsigned)a;
+  rsrc[1] = (int)((unsigned)(a >> 32) & 0xffffu);
+  rsrc[2] = (int)bytes;
+  rsrc[3] = 0x00020000;
+  const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
 // Pipelines of direct loads wait for the oldest tile only: at most N vector-memory loads of this wavefront
 // still outstanding (they complete in issue order), LDS operations done; and a barrier that does not bring
 // the wait for ALL loads with it, as __syncthreads does.

@@ -156,7 +156,7 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
                                                                   int tail_begin, int tail_splits,
                                                                   float* __restrict__ hyb_ws) {
   constexpr bool A_KC = (LAYOUT != GEMM_TN);  // A operand contiguous along K
-  constexpr bool DBUF = (LAYOUT == GEMM_TN);  // second fragment register set (measured: +7 % for TN, -4 % NN, -1 % NT)
+  constexpr bool DBUF = (LAYOUT != GEMM_NT);  // second fragment register set (measured: +3 % TN, +2-5 % NN, -1 % NT)
   constexpr bool B_KC = (LAYOUT == GEMM_NT);
   // KS == 2: two sets of WGM x WGN wavefronts share the output tile; set g multiplies the g-th half of
   // every K slab and the two accumulator sets are added through LDS before the epilogue. This doubles the
@@ -319,14 +319,21 @@ __global__ __launch_bounds__((WGM * WGN * KS + PW) * 64) void gemm_bf16_kernel(i
   const bf16_t* base_b = B + origin_b;
   const unsigned bytes_a = records((int64_t)M * K - origin_a), bytes_b = records((int64_t)N * K - origin_b);
   const int lw = __builtin_amdgcn_readfirstlane(PW ? cw - NCOMP / 64 : cw);   // index among the loading wavefronts
+  // Fragments of an operand that is not contiguous along K come through transposing reads, which the compiler would
+  // hold back behind every direct load this wavefront has in flight (common.h): those instances issue their own.
+  constexpr bool UNTRACKED = !(A_KC && B_KC) && PW == 0;
+  auto dma16 = [](const bf16_t* base, unsigned bytes, bf16_t* lds, unsigned voffset, unsigned soffset) {
+    if constexpr (UNTRACKED) buffer_load_lds_16_untracked(base, bytes, lds, voffset, soffset);
+    else buffer_load_lds_16(base, bytes, lds, voffset, soffset);
+  };
   auto load_direct = [&](int kstep, int stage) {
     bf16_t* a = sA + stage * SA + lw * 512;
     bf16_t* b = sB + stage * SB + lw * 512;
     const unsigned soa = (unsigned)(ks0 + kstep) * (unsigned)(stepA * 2), sob = (unsigned)(ks0 + kstep) * (unsigned)(stepB * 2);
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) buffer_load_lds_16(base_a, bytes_a, a + i * NTHR * 8, voa[i], soa);
+    for (int i = 0; i < A_LOADS; ++i) dma16(base_a, bytes_a, a + i * NTHR * 8, voa[i], soa);
 #pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) buffer_load_lds_16(base_b, bytes_b, b + i * NTHR * 8, vob[i], sob);
+    for (int i = 0; i < B_LOADS; ++i) dma16(base_b, bytes_b, b + i * NTHR * 8, vob[i], sob);
   };
 
   f32x16_t acc[TM][TN];
@@ -857,13 +864,13 @@ static TileKind select_tile(int layout, int M, int N, int K, bool solo) {
   // A grid of 256x256 tiles runs in rounds of 256 (one workgroup per CU) and a thin last round costs a full one:
   // 320 tiles take two rounds for 1.25 rounds of work. A GEMM that has the chip to itself (`solo`: the forward
   // pass, the exported building block) therefore takes 128x128 tiles when their round count is the cheaper one,
-  // at the long-K rates of the two kernels (PFLOP/s: 1.30 / 1.17 / 1.10 for NT / NN / TN against 1.05 / 1.0 /
+  // at the long-K rates of the two kernels (PFLOP/s: 1.30 for all three layouts against 1.05 / 1.0 /
   // 1.0; a 256x256 tile is four small ones). In the backward pass the idle CUs of a thin round are exactly where
   // the other stream's kernels run, and the same rule makes the step slower (2.7B-shaped layer: 5.39 ms against
   // 4.99 ms; on a single stream 5.06 against 5.62), so it is not applied there.
   bool big = K % 128 == 0 && t256 >= 192;
   if (solo && big && K % 256 == 0 && K >= 2048) {
-    const double e256 = layout == GEMM_NT ? 1.30 : layout == GEMM_NN ? 1.17 : 1.10, e128 = layout == GEMM_NT ? 1.05 : 1.0;
+    const double e256 = 1.30, e128 = layout == GEMM_NT ? 1.05 : 1.0;
     const double c256 = (double)((t256 + 255) / 256) * 4.0 / e256, c128 = (double)((t128 + 255) / 256) / e128;
     big = c256 <= c128;
   }
