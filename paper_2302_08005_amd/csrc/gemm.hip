@@ -832,14 +832,14 @@ __global__ __launch_bounds__(256) void hybrid_reduce_kernel(int M, int N, int ta
 template <int LAYOUT, bool F16>
 static void launch_hybrid(const HybridPlan& hp, int epi, int M, int N, int K, const void* A, const void* B, void* C,
                           const void* aux_in, float* ws, hipStream_t st) {
-  constexpr int BM = 256, BN = 256;
+  constexpr int BM = 256, BN = 256, PW = LAYOUT == GEMM_NT ? 4 : 0;   // (loader wavefronts as in the plain launch)
   const size_t lds = gemm_lds_bytes<BM, BN, 64, 2, 4, 1, 2>();
   const int grid = hp.tail_begin + hp.tail_tiles * hp.splits;
 #define SLAPO_HYB(E)                                                                                           \
   do {                                                                                                         \
-    auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, 64, 2, 4, 1, 2, 2, 0, false, E, F16, true>;                   \
+    auto kern = gemm_bf16_kernel<LAYOUT, BM, BN, 64, 2, 4, 1, 2, 2, PW, false, E, F16, true>;                  \
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);       \
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B,      \
+    hipLaunchKernelGGL(kern, dim3(grid), dim3((8 + PW) * 64), lds, st, M, N, K, (const bf16_t*)A, (const bf16_t*)B, \
                        (bf16_t*)C, (const bf16_t*)nullptr, (const bf16_t*)aux_in, (bf16_t*)nullptr, 0,         \
                        hp.tail_begin, hp.splits, ws);                                                          \
   } while (0)
@@ -851,7 +851,7 @@ static void launch_hybrid(const HybridPlan& hp, int epi, int M, int N, int K, co
 }
 
 // Tile selection, from measurements on the layer's shapes. 256x256 tiles (8 wavefronts, 128x64 each, direct
-// loads into two stages) when they still cover at least three quarters of the 256 CUs. Otherwise 128x128
+// loads into two stages, issued by four more wavefronts in the NT layout) when they still cover at least three quarters of the 256 CUs. Otherwise 128x128
 // tiles (8 wavefronts, 64x32 each): direct loads into a ring of four stages issued by four loader
 // wavefronts when K is a multiple of four slabs; else register-staged with two slabs of prefetch. For outputs with few tiles, 128x64
 // tiles: long K the same direct scheme with four computing wavefronts, else 128-deep slabs and two wave
@@ -900,7 +900,11 @@ static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, co
   }
   switch (select_tile(LAYOUT, M, N, K, solo)) {
     case TILE_256:
-      launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
+      // NT: four loader wavefronts beside the eight that compute (168 registers: three wavefronts per SIMD fit; the
+      // NN/TN instances need 190-230, so their wavefronts load their own shares)
+      if constexpr (LAYOUT == GEMM_NT) launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+      else launch_bf16_tile<LAYOUT, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st);
+      break;
     case TILE_128_SPLITSLAB:
       launch_bf16_tile<LAYOUT, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, F16>(epi, act, M, N, K, A, B, C, bias, aux_in, aux_out, st); break;
     case TILE_128_LOADERS:
@@ -1006,8 +1010,8 @@ void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool sol
   if (with_ws && !(weight_grad && weight_grad_splits(M, N, K) > 1) && select_tile(layout, M, N, K, solo) == TILE_256) {
     const HybridPlan hp = hybrid_plan(weight_grad ? EPI_NONE : epi, M, N, K);
     if (hp.ws_bytes) {
-      snprintf(buf, len, "gemm_bf16_kernel<%d, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, %d, %s, true> (%d tiles + %d tiles in %d K ranges) + hybrid_reduce_kernel",
-               layout, epi, b, hp.tail_begin, hp.tail_tiles, hp.splits);
+      snprintf(buf, len, "gemm_bf16_kernel<%d, 256, 256, 64, 2, 4, 1, 2, 2, %d, false, %d, %s, true> (%d tiles + %d tiles in %d K ranges) + hybrid_reduce_kernel",
+               layout, layout == GEMM_NT ? 4 : 0, epi, b, hp.tail_begin, hp.tail_tiles, hp.splits);
       return;
     }
   }
@@ -1024,7 +1028,8 @@ void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool sol
                                       "128, 128, 64, 2, 2, 1, 1, 0, 0, true"};
   TileKind k = select_tile(layout, M, N, K, solo);
   if (k != TILE_GENERAL && !epi_used(layout, epi)) k = TILE_GENERAL;   // epilogues the layer never pairs with this layout
-  snprintf(buf, len, "gemm_bf16_kernel<%d, %s, %d, %s, false>", layout, shape[(int)k], epi, b);
+  if (k == TILE_256 && layout == GEMM_NT) snprintf(buf, len, "gemm_bf16_kernel<0, 256, 256, 64, 2, 4, 1, 2, 2, 4, false, %d, %s, false>", epi, b);
+  else snprintf(buf, len, "gemm_bf16_kernel<%d, %s, %d, %s, false>", layout, shape[(int)k], epi, b);
 }
 
 void launch_gemm(int dtype, int layout, int epi, int act, int M, int N, int K, const void* A, const void* B,
