@@ -243,7 +243,7 @@ __global__ __launch_bounds__(WAVES * 64) void bdrln_bwd_kernel(
 // two steps' worth of rows on their way from memory: with one block per CU (the partial sums it leaves are
 // [blocks, 3, H] floats, which bounds the block count) that is what keeps the memory pipeline full. At the end
 // the groups' column sums are added in group order through LDS: one partial row per block, as above.
-template <typename T, bool LN, int R, int MAXT>
+template <typename T, bool LN, int R, int MAXT, bool ONE = false>
 __global__ __launch_bounds__(MAXT) void bdrln_bwd_wide_kernel(
     int64_t rows, int H, const T* __restrict__ dout, const T* __restrict__ z, const float* __restrict__ mu,
     const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ dres_in,
@@ -260,7 +260,8 @@ __global__ __launch_bounds__(MAXT) void bdrln_bwd_wide_kernel(
   for (int e = 0; e < 8; ++e) { pg[e] = pb[e] = pd[e] = 0.f; g[e] = 0.f; }
   if (LN && active) load8(gamma + c * 8, g);
   const int64_t per_step = (int64_t)gridDim.x * G * R;
-  const int64_t n_steps = (rows + per_step - 1) / per_step;   // the same for every group: they share the barrier
+  // (ONE: the launch covers all rows in one step; nothing is prefetched, which leaves registers for a third row)
+  const int64_t n_steps = ONE ? 1 : (rows + per_step - 1) / per_step;   // the same for every group: they share the barrier
   auto first_row = [&](int64_t step) { return ((step * gridDim.x + blockIdx.x) * G + group) * R; };
   Raw8<T> ndy[R], nz[R], nres[R];
   float nm[R], nrs[R];
@@ -539,18 +540,20 @@ static void launch_bwd(int64_t rows, int H, const void* dout, const void* z, con
     const int nw = (H / 8 + 63) / 64;
     const int groups = nw <= 6 ? (12 / nw > 8 ? 8 : 12 / nw) : 1;
     const int rows_per_group = nw <= 6 ? 2 : nw <= 8 ? 4 : 1;
-    const size_t xs_bytes = (size_t)2 * groups * rows_per_group * nw * 2 * sizeof(float);
+    const size_t xs_bytes = (size_t)2 * groups * (rows_per_group == 2 ? 3 : rows_per_group) * nw * 2 * sizeof(float);
     const size_t col_bytes = (size_t)(groups - 1) * 3 * H * sizeof(float);
     const size_t lds = xs_bytes > col_bytes ? xs_bytes : col_bytes;
-#define SLAPO_WIDE(R, MAXT)                                                                                          \
+#define SLAPO_WIDE(R, MAXT, ...)                                                                                     \
   do {                                                                                                               \
-    auto kern = bdrln_bwd_wide_kernel<T, LN, R, MAXT>;                                                               \
+    auto kern = bdrln_bwd_wide_kernel<T, LN, R, MAXT, ##__VA_ARGS__>;                                                \
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);             \
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(groups * nw * 64), lds, st, rows, H, (const T*)dout, (const T*)z, mu, \
                        rstd, (const T*)gamma, (const T*)dres_in, (T*)dz_out, (T*)dr_out, partials, dp,              \
                        dr_from_stored, nw, groups);                                                                  \
   } while (0)
-    if (nw <= 6) SLAPO_WIDE(2, 768);
+    // (three rows per group where that takes all rows in ONE step instead of a full and a thin one: 4096 rows of 1024)
+    if (nw <= 6 && rows > (int64_t)blocks * groups * 2 && rows <= (int64_t)blocks * groups * 3) SLAPO_WIDE(3, 768, true);
+    else if (nw <= 6) SLAPO_WIDE(2, 768);
     else if (nw <= 8) SLAPO_WIDE(4, 512);
     else SLAPO_WIDE(1, 1024);
 #undef SLAPO_WIDE
