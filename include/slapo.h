@@ -30,8 +30,8 @@
  *     Two calls that are given the same `scratch` or `saved` buffer must be ordered by the caller as usual.
  *   - SLAPO_DEBUG in the environment, read once at first use, is a comma-separated list of debugging / A-B
  *     timing switches: "single-stream" keeps all of backward on `stream`; "no-splitk" computes every weight
- *     gradient as one plain GEMM (and shrinks the workspace sizes reported accordingly). Nothing else in the
- *     environment changes what the library does.
+ *     gradient as one plain GEMM and "no-hybrid" every thin last round of tiles in one piece (both shrink the
+ *     workspace sizes reported accordingly). Nothing else in the environment changes what the library does.
  *   - Return value: SLAPO_OK (0) or a negative slapo_status. Argument checks run before the first
  *     HIP call, so they behave the same on a host without a GPU. Nothing throws or aborts.
  *   - Same inputs and seed give bitwise identical outputs (no floating-point atomics anywhere).

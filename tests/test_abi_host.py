@@ -200,3 +200,22 @@ def test_gemm_workspace_rules_on_the_host():
     assert lib.slapo_gemm_ex(*args, 4096 + 8, need, None) == -4
     assert lib.slapo_gemm_ex(*args[:13], 2, 4096, need, None) == -3   # unknown flag
     assert B.status_string(-5).startswith("shape needs more workspace")
+
+
+def test_debug_switches_shrink_the_reported_workspaces():
+    """SLAPO_DEBUG is read once per process: a child with the switches set reports no K-range workspaces."""
+    import subprocess
+    import sys
+    code = ("from paper_2302_08005_amd import binding as B; import workloads as W; "
+            "print(B.slapo_weight_grad_workspace(W.BF16, 1024, 1024, 16384), "
+            "B.slapo_gemm_workspace(W.BF16, B.NN, B.EPI_NONE, 4352, 4096, 2048))")
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    def run(debug):
+        env = dict(os.environ, SLAPO_DEBUG=debug)
+        out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, check=True)
+        return [int(x) for x in out.stdout.split()]
+    wg, hyb = run("")
+    assert wg > 0 and hyb > 0
+    assert run("no-splitk,no-hybrid") == [0, 0]
+    assert run("no-splitk") == [0, hyb]
