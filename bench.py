@@ -35,10 +35,10 @@ ROTATE_BYTES = 1 << 30           # the HBM-bound loops walk through at least thi
 # script (figures, scale factors and commands in profiles/), keyed by workload and kernel instance; None where
 # no counter run covers the pair.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    # profiles/layer_step_C2_bert_large_hbm_traffic.txt: 100.79 MB fetched + 7.69 MB written
-    ("C2-bert-large-layer-bf16", "gemm_bf16_kernel<2, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, 0, false, false>"): 108.48e6,
-    # profiles/layer_step_C4_gptneo_2p7b_hbm_traffic.txt: 819.28 MB fetched + 52.43 MB written
-    ("C4-gptneo-2.7b-layer-bf16", "gemm_bf16_kernel<2, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, 0, false, false>"): 871.71e6,
+    # profiles/layer_step_C2_bert_large_hbm_traffic.txt: 100.77 MB fetched + 7.69 MB written
+    ("C2-bert-large-layer-bf16", "gemm_bf16_kernel<2, 128, 128, 64, 2, 2, 2, 2, 4, 4, false, 0, false, false>"): 108.46e6,
+    # profiles/layer_step_C4_gptneo_2p7b_hbm_traffic.txt: 819.48 MB fetched + 52.43 MB written
+    ("C4-gptneo-2.7b-layer-bf16", "gemm_bf16_kernel<2, 256, 256, 64, 2, 4, 1, 2, 2, 0, false, 0, false, false>"): 871.91e6,
 }
 
 
