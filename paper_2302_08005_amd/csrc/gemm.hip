@@ -889,9 +889,9 @@ template <int LAYOUT, bool F16>
 static void launch_bf16(int epi, int act, int M, int N, int K, const void* A, const void* B, void* C,
                         const void* bias, const void* aux_in, void* aux_out, hipStream_t st, bool solo, float* ws,
                         size_t ws_bytes) {
-  if (ws && select_tile(LAYOUT, M, N, K, solo) == TILE_256) {
-    // (a GEMM that runs alone and does better with a full grid of 128x128 tiles keeps those: measured 401 against
-    // 415 us for the 8192 x 2560 x 10240 product)
+  if (ws && select_tile(LAYOUT, M, N, K, false) == TILE_256) {
+    // (with a workspace the thin last round in K ranges also beats the full grid of 128x128 tiles that a GEMM running
+    // alone would otherwise take: 359 against 397 us for the 8192 x 2560 x 10240 NT product)
     const HybridPlan hp = hybrid_plan(epi, M, N, K);
     if (hp.ws_bytes && hp.ws_bytes <= ws_bytes) {
       launch_hybrid<LAYOUT, F16>(hp, epi, M, N, K, A, B, C, aux_in, ws, st);
@@ -1007,7 +1007,7 @@ void describe_gemm(int dtype, int layout, int epi, int M, int N, int K, bool sol
   if (dtype == DT_FP32) { snprintf(buf, len, "gemm_f32_kernel<%d>", layout); return; }
   const int f16 = dtype == DT_FP16 ? 1 : 0;
   const char* b = f16 ? "true" : "false";
-  if (with_ws && !(weight_grad && weight_grad_splits(M, N, K) > 1) && select_tile(layout, M, N, K, solo) == TILE_256) {
+  if (with_ws && !(weight_grad && weight_grad_splits(M, N, K) > 1) && select_tile(layout, M, N, K, false) == TILE_256) {
     const HybridPlan hp = hybrid_plan(weight_grad ? EPI_NONE : epi, M, N, K);
     if (hp.ws_bytes) {
       snprintf(buf, len, "gemm_bf16_kernel<%d, 256, 256, 64, 2, 4, 1, 2, 2, %d, false, %d, %s, true> (%d tiles + %d tiles in %d K ranges) + hybrid_reduce_kernel",
